@@ -1,0 +1,130 @@
+/* libepp -- partially-active backward aggregation for GCN training on one MI355X (gfx950).
+ *
+ * C ABI.  Every pointer marked "device" is GPU global memory owned by the caller unless
+ * stated otherwise; "host" pointers are ordinary CPU memory.  All calls are made with the
+ * target GPU current.  Functions returning int give 0 on success or a negative EPP_ERR_*
+ * code; epp_last_error() then holds a human-readable message for the calling thread.  No
+ * function aborts or throws across this boundary.
+ *
+ * Notation (paper, Table 1 / Sec. 3 / Sec. 4): V_t training set; N^k the k-neighbour set
+ * of V_t (vertices reached from V_t by exactly k edges, N^0 = V_t); L layers; SG_l the
+ * execution path of layer l with destination vertices N^{L-l} and, for each, the
+ * neighbour list filtered by N^{L-l-1}.
+ */
+#ifndef EPP_H
+#define EPP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define EPP_OK 0
+#define EPP_ERR_INVALID_ARG (-1)     /* NULL pointer, L < 1, F < 1, negative size ...       */
+#define EPP_ERR_OUT_OF_RANGE_ID (-2) /* a training id outside [0, n)                        */
+#define EPP_ERR_TOO_LARGE (-3)       /* n or nnz >= 2^31                                    */
+#define EPP_ERR_ALLOC (-4)           /* device or host allocation failed                    */
+#define EPP_ERR_HIP (-5)             /* a HIP runtime call failed (message has the detail)  */
+
+typedef void* epp_stream_t; /* a hipStream_t; NULL = the default stream */
+
+/* Input graph: pull-mode CSR of the BACKWARD operator M (Alg. 1, backward aggregation
+ * loop: X'_v += e_vu * Y'_u for u in N(v)).  Row v lists the sources u with weight e_vu.
+ * Columns must be unique within a row (ascending order is what the synthetic inputs use;
+ * the library only relies on the order being the caller's canonical one and preserves it).
+ * Self-loops are not added: whatever is stored is the operator. */
+typedef struct {
+    int64_t n;             /* number of vertices, < 2^31                        */
+    int64_t nnz;           /* number of stored entries, < 2^31                  */
+    const int32_t* rowptr; /* device, n + 1 entries, rowptr[0] = 0              */
+    const int32_t* col;    /* device, nnz entries, each in [0, n)               */
+    const float* val;      /* device, nnz entries                               */
+} epp_csr_t;
+
+typedef struct epp_paths epp_paths_t; /* all L execution paths + the sets N^0..N^L    */
+typedef struct epp_path epp_path_t;   /* one execution path (or the all-active graph) */
+
+typedef struct {
+    int64_t n;            /* vertices of the input graph (rows of the gradient matrices)    */
+    int64_t n_rows;       /* |N^{L-l}|: destination rows of this path                       */
+    int64_t nnz;          /* entries kept                                                   */
+    int64_t n_src;        /* |N^{L-l-1}|: size of the source set                            */
+    int64_t max_len;      /* longest filtered neighbour list                                */
+    int64_t len_hist[32]; /* rows per length class c: len <= 1 -> 0, else ceil(log2(len))   */
+    int64_t bytes;        /* device bytes held by the path (canonical arrays + schedules)   */
+    /* schedule most recently used / built (0 if none yet) */
+    int32_t sched_F;        /* gradient width it was built for                              */
+    int32_t group_size;     /* gs: upper bound on entries per group (Sec. 2.2, Sec. 5)      */
+    int64_t n_groups;       /* sum over rows of ceil(len / gs) (rows of length 0 count 1)   */
+    int64_t n_split_rows;   /* rows cut into more than one group (written with atomics)     */
+} epp_path_info_t;
+
+/* Execution path preparing (Sec. 4): computes N^k for k = 0..L (Theorem 1) by backward
+ * frontier expansion from train_ids, and for every layer l the sub-graph SG_l in compact
+ * CSR (rows ascending by vertex id, entries in input order, original column ids).
+ *   g          host struct with device arrays (read only during the call)
+ *   train_ids  device, n_train entries; duplicates allowed (set semantics)
+ *   L          number of layers, >= 1
+ *   stream     work is enqueued here; the call synchronises the stream before returning
+ *   out        receives a handle owned by the library; release with epp_destroy_paths
+ * n_train = 0 is valid (all paths empty).  Any id outside [0, n): EPP_ERR_OUT_OF_RANGE_ID. */
+int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t n_train, int L,
+                epp_stream_t stream, epp_paths_t** out);
+
+/* The all-active baseline (Alg. 1, backward aggregation over every vertex of the input
+ * graph) wrapped as a "path" whose rows are all n vertices, so that the same kernels run
+ * it.  Copies what it needs; g may be freed afterwards. */
+int epp_prepare_full(const epp_csr_t* g, epp_stream_t stream, epp_path_t** out);
+
+int epp_num_layers(const epp_paths_t* p);
+/* Path of layer l in [0, L) as numbered in Alg. 2 (layer L-1 runs first in an epoch).
+ * Borrowed pointer, valid until epp_destroy_paths.  NULL if l is out of range. */
+epp_path_t* epp_get_path(epp_paths_t* p, int l);
+
+int epp_path_info(const epp_path_t* p, epp_path_info_t* info /* host */);
+
+/* Canonical form of a path into caller buffers (device): row_ids[n_rows], rowptr[n_rows+1],
+ * col[nnz], val[nnz]; any of the four may be NULL to skip it.  Synchronises the stream. */
+int epp_path_export(const epp_path_t* p, int32_t* row_ids, int32_t* rowptr, int32_t* col, float* val,
+                    epp_stream_t stream);
+
+/* N^k (k in [0, L]) as ascending vertex ids.  ids (device, may be NULL to query the size
+ * only) must hold *count entries; count (host) receives |N^k|.  Synchronises the stream. */
+int epp_active_set_export(const epp_paths_t* p, int k, int32_t* ids, int64_t* count, epp_stream_t stream);
+
+/* Structure-aware group size (Sec. 5, re-derived for 64-lane wavefronts): the upper bound
+ * gs on entries per group that this library picks for gradient width F from the path's
+ * row-length histogram.  Pure function of (path, F); returns gs >= 1 or a negative error. */
+int epp_select_group_size(const epp_path_t* p, int F);
+
+/* Force the group size used for width F (sweeps, ablations); gs <= 0 restores the selector.
+ * Rebuilds the group table (neighbour grouping, Sec. 2.2: each row is cut into consecutive
+ * groups of at most gs entries).  lanes_per_row_hint: 0 = automatic; otherwise the maximal
+ * number of lanes that cooperate on one group, a power of two <= 64.  Synchronises. */
+int epp_path_set_group_size(epp_path_t* p, int F, int gs, int lanes_per_row_hint, epp_stream_t stream);
+
+/* Partially-active backward aggregation of one layer (Alg. 2, aggregation loop):
+ *     grad_out[v, :] = sum over entries (u, e_vu) of row v in SG_l of  e_vu * grad_in[u, :]
+ * for every destination vertex v of the path.
+ *   grad_in, grad_out   device, row-major n x F fp32 (leading dimension F), not aliased
+ *   rows of grad_out outside the path are NOT touched (zero them once; the active sets never
+ *   change across epochs); rows of grad_in outside the source set are never read.
+ * Asynchronous on `stream` except for the first call with a new (path, F), which builds the
+ * group schedule and synchronises once. */
+int epp_backward_aggregate(epp_path_t* p, const float* grad_in, float* grad_out, int F, epp_stream_t stream);
+
+/* All-active backward aggregation (Alg. 1) over a handle from epp_prepare_full: writes
+ * every one of the n rows of grad_out (rows with empty lists become zero). */
+int epp_full_aggregate(epp_path_t* full, const float* grad_in, float* grad_out, int F, epp_stream_t stream);
+
+void epp_destroy_paths(epp_paths_t* p);
+void epp_destroy_path(epp_path_t* p); /* only for handles from epp_prepare_full */
+
+const char* epp_last_error(void); /* thread-local, never NULL */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EPP_H */

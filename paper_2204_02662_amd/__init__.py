@@ -1,0 +1,224 @@
+"""Thin Python binding of libepp (C ABI, see include/epp.h).
+
+Argument marshalling only: every step of the path runs inside the HIP library.  PyTorch
+supplies device memory (tensors) and the current stream.  There is no CPU fallback: if the
+shared library is missing or cannot be loaded, importing the functions below raises.
+"""
+from __future__ import annotations
+
+import ctypes
+from dataclasses import dataclass
+from pathlib import Path
+
+import torch
+
+PKG = Path(__file__).resolve().parent
+SO = PKG / "libepp.so"
+
+EPP_OK = 0
+EPP_ERR_INVALID_ARG = -1
+EPP_ERR_OUT_OF_RANGE_ID = -2
+EPP_ERR_TOO_LARGE = -3
+EPP_ERR_ALLOC = -4
+EPP_ERR_HIP = -5
+
+EXPORTED = [
+    "epp_prepare", "epp_prepare_full", "epp_num_layers", "epp_get_path", "epp_path_info",
+    "epp_path_export", "epp_active_set_export", "epp_select_group_size", "epp_path_set_group_size",
+    "epp_backward_aggregate", "epp_full_aggregate", "epp_destroy_paths", "epp_destroy_path",
+    "epp_last_error",
+]
+
+
+class EppError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"libepp error {code}: {message}")
+        self.code = code
+
+
+class _Csr(ctypes.Structure):
+    _fields_ = [("n", ctypes.c_int64), ("nnz", ctypes.c_int64), ("rowptr", ctypes.c_void_p),
+                ("col", ctypes.c_void_p), ("val", ctypes.c_void_p)]
+
+
+class _PathInfo(ctypes.Structure):
+    _fields_ = [("n", ctypes.c_int64), ("n_rows", ctypes.c_int64), ("nnz", ctypes.c_int64),
+                ("n_src", ctypes.c_int64), ("max_len", ctypes.c_int64), ("len_hist", ctypes.c_int64 * 32),
+                ("bytes", ctypes.c_int64), ("sched_F", ctypes.c_int32), ("group_size", ctypes.c_int32),
+                ("n_groups", ctypes.c_int64), ("n_split_rows", ctypes.c_int64)]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libepp.so (built by ``paper_2204_02662_amd.build``); raises if it is absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not SO.exists():
+        raise FileNotFoundError(f"{SO} not built: run `python -m paper_2204_02662_amd.build`")
+    lib = ctypes.CDLL(str(SO))
+    P, I, I64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
+    lib.epp_prepare.argtypes = [ctypes.POINTER(_Csr), P, I64, I, P, ctypes.POINTER(P)]
+    lib.epp_prepare_full.argtypes = [ctypes.POINTER(_Csr), P, ctypes.POINTER(P)]
+    lib.epp_num_layers.argtypes = [P]
+    lib.epp_get_path.argtypes = [P, I]
+    lib.epp_get_path.restype = P
+    lib.epp_path_info.argtypes = [P, ctypes.POINTER(_PathInfo)]
+    lib.epp_path_export.argtypes = [P, P, P, P, P, P]
+    lib.epp_active_set_export.argtypes = [P, I, P, ctypes.POINTER(I64), P]
+    lib.epp_select_group_size.argtypes = [P, I]
+    lib.epp_path_set_group_size.argtypes = [P, I, I, I, P]
+    lib.epp_backward_aggregate.argtypes = [P, P, P, I, P]
+    lib.epp_full_aggregate.argtypes = [P, P, P, I, P]
+    lib.epp_destroy_paths.argtypes = [P]
+    lib.epp_destroy_paths.restype = None
+    lib.epp_destroy_path.argtypes = [P]
+    lib.epp_destroy_path.restype = None
+    lib.epp_last_error.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(rc: int) -> int:
+    if rc < 0:
+        raise EppError(rc, load_library().epp_last_error().decode())
+    return rc
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t: torch.Tensor, dtype) -> torch.Tensor:
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise ValueError(f"expected a contiguous CUDA tensor of {dtype}, got {t.dtype} on {t.device}")
+    return t
+
+
+def _csr(n, rowptr, col, val):
+    _dev(rowptr, torch.int32), _dev(col, torch.int32), _dev(val, torch.float32)
+    if rowptr.numel() != n + 1 or col.numel() != val.numel():
+        raise ValueError("inconsistent CSR arrays")
+    return _Csr(n, col.numel(), rowptr.data_ptr(), col.data_ptr(), val.data_ptr())
+
+
+@dataclass
+class PathInfo:
+    n: int
+    n_rows: int
+    nnz: int
+    n_src: int
+    max_len: int
+    len_hist: list
+    bytes: int
+    sched_F: int
+    group_size: int
+    n_groups: int
+    n_split_rows: int
+
+
+class Path_:
+    """One execution path SG_l (or the all-active graph).  Borrowed from a Paths object
+    unless ``owned``."""
+
+    def __init__(self, handle: int, owned: bool, keepalive=None):
+        self._h = handle
+        self._owned = owned
+        self._keepalive = keepalive
+
+    def info(self) -> PathInfo:
+        raw = _PathInfo()
+        _check(load_library().epp_path_info(self._h, ctypes.byref(raw)))
+        return PathInfo(raw.n, raw.n_rows, raw.nnz, raw.n_src, raw.max_len, list(raw.len_hist), raw.bytes,
+                        raw.sched_F, raw.group_size, raw.n_groups, raw.n_split_rows)
+
+    def export(self):
+        """(row_ids, rowptr, col, val) device tensors in canonical form."""
+        i = self.info()
+        dev = torch.device("cuda", torch.cuda.current_device())
+        row_ids = torch.empty(i.n_rows, dtype=torch.int32, device=dev)
+        rowptr = torch.empty(i.n_rows + 1, dtype=torch.int32, device=dev)
+        col = torch.empty(i.nnz, dtype=torch.int32, device=dev)
+        val = torch.empty(i.nnz, dtype=torch.float32, device=dev)
+        _check(load_library().epp_path_export(self._h, row_ids.data_ptr(), rowptr.data_ptr(), col.data_ptr(),
+                                              val.data_ptr(), _stream()))
+        return row_ids, rowptr, col, val
+
+    def select_group_size(self, F: int) -> int:
+        return _check(load_library().epp_select_group_size(self._h, F))
+
+    def set_group_size(self, F: int, gs: int, lanes_per_row_hint: int = 0) -> None:
+        _check(load_library().epp_path_set_group_size(self._h, F, gs, lanes_per_row_hint, _stream()))
+
+    def __del__(self):
+        if getattr(self, "_owned", False) and self._h:
+            load_library().epp_destroy_path(self._h)
+            self._h = None
+
+
+class Paths:
+    """All L execution paths and the sets N^0..N^L (handle from epp_prepare)."""
+
+    def __init__(self, handle: int):
+        self._h = handle
+
+    @property
+    def num_layers(self) -> int:
+        return _check(load_library().epp_num_layers(self._h))
+
+    def path(self, l: int) -> Path_:
+        h = load_library().epp_get_path(self._h, l)
+        if not h:
+            raise EppError(EPP_ERR_INVALID_ARG, load_library().epp_last_error().decode())
+        return Path_(h, owned=False, keepalive=self)
+
+    def active_set(self, k: int) -> torch.Tensor:
+        """Ascending vertex ids of N^k (device int32 tensor)."""
+        lib = load_library()
+        cnt = ctypes.c_int64(0)
+        _check(lib.epp_active_set_export(self._h, k, None, ctypes.byref(cnt), _stream()))
+        ids = torch.empty(cnt.value, dtype=torch.int32, device=torch.device("cuda", torch.cuda.current_device()))
+        _check(lib.epp_active_set_export(self._h, k, ids.data_ptr(), ctypes.byref(cnt), _stream()))
+        return ids
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            load_library().epp_destroy_paths(self._h)
+            self._h = None
+
+
+def epp_prepare(n: int, rowptr: torch.Tensor, col: torch.Tensor, val: torch.Tensor, train_ids: torch.Tensor,
+                L: int) -> Paths:
+    lib = load_library()
+    csr = _csr(n, rowptr, col, val)
+    _dev(train_ids, torch.int32)
+    out = ctypes.c_void_p()
+    _check(lib.epp_prepare(ctypes.byref(csr), train_ids.data_ptr(), train_ids.numel(), L, _stream(), ctypes.byref(out)))
+    return Paths(out.value)
+
+
+def epp_prepare_full(n: int, rowptr: torch.Tensor, col: torch.Tensor, val: torch.Tensor) -> Path_:
+    lib = load_library()
+    csr = _csr(n, rowptr, col, val)
+    out = ctypes.c_void_p()
+    _check(lib.epp_prepare_full(ctypes.byref(csr), _stream(), ctypes.byref(out)))
+    return Path_(out.value, owned=True)
+
+
+def _grads(path: Path_, grad_in: torch.Tensor, grad_out: torch.Tensor) -> int:
+    _dev(grad_in, torch.float32), _dev(grad_out, torch.float32)
+    if grad_in.dim() != 2 or grad_in.shape != grad_out.shape:
+        raise ValueError("grad_in and grad_out must be n x F matrices of the same shape")
+    return grad_in.shape[1]
+
+
+def epp_backward_aggregate(path: Path_, grad_in: torch.Tensor, grad_out: torch.Tensor) -> None:
+    F = _grads(path, grad_in, grad_out)
+    _check(load_library().epp_backward_aggregate(path._h, grad_in.data_ptr(), grad_out.data_ptr(), F, _stream()))
+
+
+def epp_full_aggregate(full: Path_, grad_in: torch.Tensor, grad_out: torch.Tensor) -> None:
+    F = _grads(full, grad_in, grad_out)
+    _check(load_library().epp_full_aggregate(full._h, grad_in.data_ptr(), grad_out.data_ptr(), F, _stream()))

@@ -1,0 +1,120 @@
+// C-ABI entry points that tie paths, schedules and kernels together.
+
+#include <cstdarg>
+#include <cstring>
+
+#include "epp_internal.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+epp_path::WidthCfg* width_cfg(epp_path* p, int F) {
+    for (auto& w : p->widths)
+        if (w.F == F) return &w;
+    p->widths.push_back(epp_path::WidthCfg{F, 0, 0, nullptr});
+    return &p->widths.back();
+}
+
+Schedule* find_schedule(epp_path* p, int gs) {
+    for (Schedule* s : p->scheds)
+        if (s->gs == gs) return s;
+    return nullptr;
+}
+
+int ensure_schedule(epp_path* p, int F, hipStream_t s, epp_path::WidthCfg** out) {
+    epp_path::WidthCfg* w = width_cfg(p, F);
+    if (!w->sched) {
+        const int gs = w->forced_gs > 0 ? w->forced_gs : epp_default_group_size(p, F);
+        Schedule* sc = find_schedule(p, gs);
+        if (!sc) EPP_TRY(epp_build_schedule(p, gs, s, &sc));
+        w->sched = sc;
+    }
+    p->last_F = F;
+    *out = w;
+    return EPP_OK;
+}
+
+int aggregate(epp_path* p, const float* in, float* out, int F, hipStream_t s) {
+    if (!p || !in || !out) { epp_set_error("NULL argument"); return EPP_ERR_INVALID_ARG; }
+    if (F < 1) { epp_set_error("F must be >= 1 (got %d)", F); return EPP_ERR_INVALID_ARG; }
+    if ((int64_t)p->n * F >= (1ll << 40)) { epp_set_error("gradient matrix too large"); return EPP_ERR_TOO_LARGE; }
+    if (in == out) { epp_set_error("grad_in and grad_out must not alias"); return EPP_ERR_INVALID_ARG; }
+    epp_path::WidthCfg* w = nullptr;
+    EPP_TRY(ensure_schedule(p, F, s, &w));
+    return epp_launch_aggregate(p, w->sched, w->lanes_hint, in, out, F, s);
+}
+
+}  // namespace
+
+void epp_set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+extern "C" const char* epp_last_error(void) { return g_err; }
+
+extern "C" int epp_path_info(const epp_path_t* p, epp_path_info_t* info) {
+    if (!p || !info) { epp_set_error("NULL argument"); return EPP_ERR_INVALID_ARG; }
+    std::memset(info, 0, sizeof(*info));
+    info->n = p->n;
+    info->n_rows = p->n_rows;
+    info->nnz = p->nnz;
+    info->n_src = p->n_src;
+    info->max_len = p->max_len;
+    for (int c = 0; c < EPP_NCLASS; ++c) info->len_hist[c] = p->len_hist[c];
+    size_t bytes = p->row_ids.bytes + p->rowptr.bytes + p->cv.bytes;
+    for (const Schedule* s : p->scheds) bytes += s->bytes();
+    info->bytes = (int64_t)bytes;
+    for (const auto& w : p->widths) {
+        if (w.F == p->last_F && w.sched) {
+            info->sched_F = w.F;
+            info->group_size = w.sched->gs;
+            info->n_groups = w.sched->n_groups;
+            info->n_split_rows = w.sched->n_split_rows;
+        }
+    }
+    return EPP_OK;
+}
+
+extern "C" int epp_select_group_size(const epp_path_t* p, int F) {
+    if (!p) { epp_set_error("path is NULL"); return EPP_ERR_INVALID_ARG; }
+    if (F < 1) { epp_set_error("F must be >= 1"); return EPP_ERR_INVALID_ARG; }
+    return epp_default_group_size(p, F);
+}
+
+extern "C" int epp_path_set_group_size(epp_path_t* p, int F, int gs, int lanes_per_row_hint, epp_stream_t stream) {
+    if (!p) { epp_set_error("path is NULL"); return EPP_ERR_INVALID_ARG; }
+    if (F < 1) { epp_set_error("F must be >= 1"); return EPP_ERR_INVALID_ARG; }
+    if (lanes_per_row_hint < 0 || lanes_per_row_hint > 64 || (lanes_per_row_hint & (lanes_per_row_hint - 1))) {
+        epp_set_error("lanes_per_row_hint must be 0 or a power of two <= 64");
+        return EPP_ERR_INVALID_ARG;
+    }
+    epp_path::WidthCfg* w = width_cfg(p, F);
+    w->forced_gs = gs > 0 ? gs : 0;
+    w->lanes_hint = lanes_per_row_hint;
+    w->sched = nullptr;
+    // drop cached tables that no width refers to any more
+    for (size_t i = 0; i < p->scheds.size();) {
+        bool used = false;
+        for (const auto& x : p->widths) used |= (x.sched == p->scheds[i]);
+        if (!used) { delete p->scheds[i]; p->scheds.erase(p->scheds.begin() + i); } else ++i;
+    }
+    return ensure_schedule(p, F, (hipStream_t)stream, &w);
+}
+
+extern "C" int epp_backward_aggregate(epp_path_t* p, const float* grad_in, float* grad_out, int F,
+                                      epp_stream_t stream) {
+    return aggregate(p, grad_in, grad_out, F, (hipStream_t)stream);
+}
+
+extern "C" int epp_full_aggregate(epp_path_t* full, const float* grad_in, float* grad_out, int F,
+                                  epp_stream_t stream) {
+    if (full && !full->all_rows) {
+        epp_set_error("epp_full_aggregate needs a handle from epp_prepare_full");
+        return EPP_ERR_INVALID_ARG;
+    }
+    return aggregate(full, grad_in, grad_out, F, (hipStream_t)stream);
+}

@@ -1,0 +1,516 @@
+// Execution path preparing on the GPU (Sec. 4): frontier expansion from the training set
+// (Theorem 1's sets N^k), stable extraction of the filtered neighbour lists, row
+// renumbering and prefix-sum compaction into compact CSR.  Hand-written for gfx950, wave64.
+//
+// One level k -> k+1 is two streaming passes over the edge array and two over the rows:
+//   edge_mask     keep[j] = (col[j] in N^k) as one 64-bit ballot per 64 edges + tile counts
+//   scan          exclusive scan of the tile counts (one readback: nnz of the path)
+//   edge_extract  stable compaction of (col, val) through the ballots; also stores the
+//                 running count at every 64-edge boundary
+//   row_flags     filtered row pointer of every vertex from those counts; a vertex is in
+//                 N^{k+1} iff its filtered list is non-empty -> next bitmap
+//   bitmap_count / scan / bitmap_compact   ascending ids of N^{k+1} + compact row pointer
+// All kept entries belong to rows of N^{k+1} by definition, so compacting the edge array
+// alone yields the path's entries in canonical order.
+
+#include <algorithm>
+#include <cstring>
+
+#include "epp_internal.h"
+
+namespace {
+
+constexpr int kBlock = 256;
+constexpr int kSegsPerTile = 32;  // 32 ballots of 64 edges = 2048 edges per workgroup
+constexpr int kWordsPerTile = 256;
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
+__device__ __forceinline__ unsigned long long low_mask(int lane) { return (1ull << lane) - 1ull; }
+
+// Inclusive scan across the 64 lanes of a wavefront.
+__device__ __forceinline__ int wave_inclusive_scan(int x) {
+    const int lane = lane_id();
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        int y = __shfl_up(x, d, 64);
+        if (lane >= d) x += y;
+    }
+    return x;
+}
+
+// Exclusive scan over the 256 threads of a workgroup; *total receives the block sum.
+__device__ __forceinline__ int block_exclusive_scan(int x, int* total) {
+    __shared__ int wave_sum[4];
+    const int wave = threadIdx.x >> 6, lane = lane_id();
+    int incl = wave_inclusive_scan(x);
+    if (lane == 63) wave_sum[wave] = incl;
+    __syncthreads();
+    int base = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        if (w < wave) base += wave_sum[w];
+        all += wave_sum[w];
+    }
+    __syncthreads();
+    *total = all;
+    return base + incl - x;
+}
+
+// N^0 = V_t as a bitmap; ids outside [0, n) raise the error flag instead of being written.
+__global__ __launch_bounds__(kBlock) void k_mark_training(const int32_t* __restrict__ ids, int64_t n_ids, int64_t n,
+                                                          unsigned int* __restrict__ bitmap32,
+                                                          int* __restrict__ err) {
+    int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= n_ids) return;
+    int32_t v = ids[i];
+    if (v < 0 || v >= n) { atomicOr(err, 1); return; }
+    atomicOr(&bitmap32[v >> 5], 1u << (v & 31));
+}
+
+// keep-mask of every 64-edge segment and kept entries per tile.
+__global__ __launch_bounds__(kBlock) void k_edge_mask(const int32_t* __restrict__ col, int64_t nnz, int64_t n_seg,
+                                                      const unsigned int* __restrict__ bitmap32,
+                                                      unsigned long long* __restrict__ mask,
+                                                      int* __restrict__ tile_count) {
+    __shared__ int wave_cnt[4];
+    const int wave = threadIdx.x >> 6, lane = lane_id();
+    int cnt = 0;
+    for (int i = wave; i < kSegsPerTile; i += 4) {
+        int64_t seg = (int64_t)blockIdx.x * kSegsPerTile + i;
+        int64_t e = seg * 64 + lane;
+        bool keep = false;
+        if (e < nnz) {
+            int32_t c = col[e];
+            keep = (bitmap32[c >> 5] >> (c & 31)) & 1u;
+        }
+        unsigned long long m = __ballot(keep);
+        if (lane == 0 && seg < n_seg) mask[seg] = m;
+        cnt += __popcll(m);
+    }
+    if (lane == 0) wave_cnt[wave] = cnt;
+    __syncthreads();
+    if (threadIdx.x == 0) tile_count[blockIdx.x] = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+}
+
+// Single-workgroup exclusive scan of `n` counts (n is at most a few hundred thousand).
+__global__ __launch_bounds__(1024) void k_scan_counts(const int* __restrict__ in, int* __restrict__ out, int64_t n,
+                                                      long long* __restrict__ total) {
+    __shared__ int wave_sum[16];
+    __shared__ int carry_s;
+    const int wave = threadIdx.x >> 6, lane = lane_id();
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+    for (int64_t base = 0; base < n; base += 1024) {
+        int64_t i = base + threadIdx.x;
+        int x = i < n ? in[i] : 0;
+        int incl = wave_inclusive_scan(x);
+        if (lane == 63) wave_sum[wave] = incl;
+        __syncthreads();
+        int off = carry_s, all = 0;
+        for (int w = 0; w < 16; ++w) {
+            if (w < wave) off += wave_sum[w];
+            all += wave_sum[w];
+        }
+        if (i < n) out[i] = off + incl - x;
+        __syncthreads();
+        if (threadIdx.x == 0) carry_s += all;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *total = carry_s;
+}
+
+// Stable compaction of the kept entries into interleaved (col, val) pairs; seg_base[s]
+// receives the number of kept entries before segment s.
+__global__ __launch_bounds__(kBlock) void k_edge_extract(const int32_t* __restrict__ col, const float* __restrict__ val,
+                                                         int64_t n_seg, const unsigned long long* __restrict__ mask,
+                                                         const int* __restrict__ tile_base,
+                                                         int* __restrict__ seg_base, int2* __restrict__ cv) {
+    __shared__ int sbase[kSegsPerTile];
+    const int wave = threadIdx.x >> 6, lane = lane_id();
+    if (wave == 0) {
+        int64_t seg = (int64_t)blockIdx.x * kSegsPerTile + lane;
+        int c = (lane < kSegsPerTile && seg < n_seg) ? __popcll(mask[seg]) : 0;
+        int incl = wave_inclusive_scan(c);
+        if (lane < kSegsPerTile) {
+            int b = tile_base[blockIdx.x] + incl - c;
+            sbase[lane] = b;
+            if (seg < n_seg) seg_base[seg] = b;
+        }
+    }
+    __syncthreads();
+    for (int i = wave; i < kSegsPerTile; i += 4) {
+        int64_t seg = (int64_t)blockIdx.x * kSegsPerTile + i;
+        if (seg >= n_seg) break;
+        unsigned long long m = mask[seg];
+        if ((m >> lane) & 1ull) {
+            int64_t e = seg * 64 + lane;
+            int pos = sbase[i] + __popcll(m & low_mask(lane));
+            cv[pos] = make_int2(col[e], __float_as_int(val[e]));
+        }
+    }
+}
+
+// Filtered row pointer of every vertex and membership of N^{k+1}.
+__global__ __launch_bounds__(kBlock) void k_row_flags(const int32_t* __restrict__ rowptr, int64_t n, int64_t nnz,
+                                                      const unsigned long long* __restrict__ mask,
+                                                      const int* __restrict__ seg_base, int total,
+                                                      int* __restrict__ newptr,
+                                                      unsigned long long* __restrict__ bitmap_next) {
+    int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    bool flag = false;
+    if (v < n) {
+        int64_t p0 = rowptr[v], p1 = rowptr[v + 1];
+        int a = p0 >= nnz ? total : seg_base[p0 >> 6] + __popcll(mask[p0 >> 6] & low_mask((int)(p0 & 63)));
+        int b = p1 >= nnz ? total : seg_base[p1 >> 6] + __popcll(mask[p1 >> 6] & low_mask((int)(p1 & 63)));
+        newptr[v] = a;
+        if (v == n - 1) newptr[n] = b;
+        flag = b > a;
+    }
+    unsigned long long bal = __ballot(flag);
+    if (lane_id() == 0 && (v >> 6) < ((n + 63) >> 6)) bitmap_next[v >> 6] = bal;
+}
+
+__global__ __launch_bounds__(kBlock) void k_bitmap_count(const unsigned long long* __restrict__ bitmap, int64_t n_words,
+                                                         int* __restrict__ tile_count) {
+    int64_t w = (int64_t)blockIdx.x * kWordsPerTile + threadIdx.x;
+    int c = w < n_words ? __popcll(bitmap[w]) : 0;
+    int total;
+    (void)block_exclusive_scan(c, &total);
+    if (threadIdx.x == 0) tile_count[blockIdx.x] = total;
+}
+
+// Ascending ids of the set bits; optionally the compact row pointer gathered from newptr.
+__global__ __launch_bounds__(kBlock) void k_bitmap_compact(const unsigned long long* __restrict__ bitmap,
+                                                           int64_t n_words, const int* __restrict__ tile_base,
+                                                           const int* __restrict__ newptr, int32_t* __restrict__ ids,
+                                                           int32_t* __restrict__ ptr_out, int64_t n_set,
+                                                           int total_nnz) {
+    __shared__ int wbase[kWordsPerTile];
+    int64_t w = (int64_t)blockIdx.x * kWordsPerTile + threadIdx.x;
+    int c = w < n_words ? __popcll(bitmap[w]) : 0;
+    int total;
+    wbase[threadIdx.x] = block_exclusive_scan(c, &total);
+    __syncthreads();
+    const int wave = threadIdx.x >> 6, lane = lane_id();
+    const int tb = tile_base[blockIdx.x];
+    for (int i = wave; i < kWordsPerTile; i += 4) {
+        int64_t ww = (int64_t)blockIdx.x * kWordsPerTile + i;
+        if (ww >= n_words) break;
+        unsigned long long m = bitmap[ww];
+        if ((m >> lane) & 1ull) {
+            int r = tb + wbase[i] + __popcll(m & low_mask(lane));
+            int32_t v = (int32_t)(ww * 64 + lane);
+            ids[r] = v;
+            if (ptr_out) ptr_out[r] = newptr[v];
+        }
+    }
+    if (ptr_out && blockIdx.x == 0 && threadIdx.x == 0) ptr_out[n_set] = total_nnz;
+}
+
+__device__ __forceinline__ int length_class(int len) { return len <= 1 ? 0 : 32 - __clz(len - 1); }
+
+// Row-length histogram by class and the maximal length.
+__global__ __launch_bounds__(kBlock) void k_len_hist(const int32_t* __restrict__ rowptr, int64_t n_rows,
+                                                     unsigned long long* __restrict__ hist, int* __restrict__ max_len) {
+    __shared__ int h[EPP_NCLASS];
+    __shared__ int mx;
+    if (threadIdx.x < EPP_NCLASS) h[threadIdx.x] = 0;
+    if (threadIdx.x == 0) mx = 0;
+    __syncthreads();
+    int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (r < n_rows) {
+        int len = rowptr[r + 1] - rowptr[r];
+        atomicAdd(&h[length_class(len)], 1);
+        atomicMax(&mx, len);
+    }
+    __syncthreads();
+    if (threadIdx.x < EPP_NCLASS && h[threadIdx.x]) atomicAdd(&hist[threadIdx.x], (unsigned long long)h[threadIdx.x]);
+    if (threadIdx.x == 0 && mx) atomicMax(max_len, mx);
+}
+
+// Interleave a plain CSR's (col, val) into pairs (all-active graph).
+__global__ __launch_bounds__(kBlock) void k_interleave(const int32_t* __restrict__ col, const float* __restrict__ val,
+                                                       int64_t nnz, int2* __restrict__ cv) {
+    int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (e < nnz) cv[e] = make_int2(col[e], __float_as_int(val[e]));
+}
+
+__global__ __launch_bounds__(kBlock) void k_deinterleave(const int2* __restrict__ cv, int64_t nnz, int32_t* __restrict__ col,
+                                                         float* __restrict__ val) {
+    int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (e < nnz) {
+        int2 x = cv[e];
+        if (col) col[e] = x.x;
+        if (val) val[e] = __int_as_float(x.y);
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_iota(int32_t* __restrict__ out, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i < n) out[i] = (int32_t)i;
+}
+
+inline unsigned grid_for(int64_t n, int per_block) { return (unsigned)((n + per_block - 1) / per_block); }
+
+// Pinned host staging for the few scalars read back per level.
+struct HostScalars {
+    long long* p = nullptr;
+    int init() {
+        if (hipHostMalloc((void**)&p, 64 * sizeof(long long), hipHostMallocDefault) != hipSuccess) {
+            (void)hipGetLastError();
+            epp_set_error("pinned host allocation failed");
+            return EPP_ERR_ALLOC;
+        }
+        return EPP_OK;
+    }
+    ~HostScalars() { if (p) (void)hipHostFree(p); }
+};
+
+int validate_csr(const epp_csr_t* g) {
+    if (!g) { epp_set_error("graph is NULL"); return EPP_ERR_INVALID_ARG; }
+    if (g->n < 0 || g->nnz < 0) { epp_set_error("negative graph size"); return EPP_ERR_INVALID_ARG; }
+    if (g->n >= 0x7FFFFFFFll || g->nnz >= 0x7FFFFFFFll) {
+        epp_set_error("graph too large: n=%lld nnz=%lld (limit 2^31-1)", (long long)g->n, (long long)g->nnz);
+        return EPP_ERR_TOO_LARGE;
+    }
+    if (!g->rowptr || (g->nnz > 0 && (!g->col || !g->val))) {
+        epp_set_error("graph arrays are NULL");
+        return EPP_ERR_INVALID_ARG;
+    }
+    return EPP_OK;
+}
+
+// Ascending ids of a bitmap (and optionally the compact row pointer).  Returns the count.
+int compact_bitmap(const DevBuf& bitmap, int64_t n, const int* newptr, int total_nnz, DevBuf* ids, DevBuf* ptr_out,
+                   int64_t* count, DevBuf& tile_cnt, DevBuf& tile_base, DevBuf& dev_total, HostScalars& hs,
+                   hipStream_t s) {
+    const int64_t n_words = (n + 63) / 64;
+    const unsigned tiles = grid_for(n_words, kWordsPerTile);
+    long long R = 0;
+    if (tiles) {
+        hipLaunchKernelGGL(k_bitmap_count, dim3(tiles), dim3(kBlock), 0, s, bitmap.as<unsigned long long>(), n_words,
+                           tile_cnt.as<int>());
+        hipLaunchKernelGGL(k_scan_counts, dim3(1), dim3(1024), 0, s, tile_cnt.as<int>(), tile_base.as<int>(),
+                           (int64_t)tiles, dev_total.as<long long>());
+        EPP_HIP_TRY(hipMemcpyAsync(hs.p, dev_total.p, sizeof(long long), hipMemcpyDeviceToHost, s));
+        EPP_HIP_TRY(hipStreamSynchronize(s));
+        R = hs.p[0];
+    }
+    *count = R;
+    if (!ids) return EPP_OK;
+    EPP_TRY(ids->alloc((size_t)R * sizeof(int32_t)));
+    if (ptr_out) EPP_TRY(ptr_out->alloc((size_t)(R + 1) * sizeof(int32_t)));
+    if (tiles) {
+        hipLaunchKernelGGL(k_bitmap_compact, dim3(tiles), dim3(kBlock), 0, s, bitmap.as<unsigned long long>(), n_words,
+                           tile_base.as<int>(), newptr, ids->as<int32_t>(),
+                           ptr_out ? ptr_out->as<int32_t>() : nullptr, (int64_t)R, total_nnz);
+    } else if (ptr_out) {
+        EPP_HIP_TRY(hipMemsetAsync(ptr_out->p, 0, sizeof(int32_t), s));
+    }
+    EPP_HIP_TRY(hipGetLastError());
+    return EPP_OK;
+}
+
+}  // namespace
+
+int epp_path_finish(epp_path* p, hipStream_t s) {
+    DevBuf stats;
+    EPP_TRY(stats.alloc((EPP_NCLASS + 1) * sizeof(unsigned long long)));
+    EPP_HIP_TRY(hipMemsetAsync(stats.p, 0, stats.bytes, s));
+    if (p->n_rows > 0) {
+        hipLaunchKernelGGL(k_len_hist, dim3(grid_for(p->n_rows, kBlock)), dim3(kBlock), 0, s, p->rowptr.as<int32_t>(),
+                           p->n_rows, stats.as<unsigned long long>(),
+                           reinterpret_cast<int*>(stats.as<unsigned long long>() + EPP_NCLASS));
+        EPP_HIP_TRY(hipGetLastError());
+    }
+    unsigned long long host[EPP_NCLASS + 1];
+    EPP_HIP_TRY(hipMemcpyAsync(host, stats.p, sizeof(host), hipMemcpyDeviceToHost, s));
+    EPP_HIP_TRY(hipStreamSynchronize(s));
+    for (int c = 0; c < EPP_NCLASS; ++c) p->len_hist[c] = (int64_t)host[c];
+    int mx;
+    std::memcpy(&mx, &host[EPP_NCLASS], sizeof(int));
+    p->max_len = mx;
+    return EPP_OK;
+}
+
+extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t n_train, int L,
+                           epp_stream_t stream, epp_paths_t** out) {
+    if (!out) { epp_set_error("out is NULL"); return EPP_ERR_INVALID_ARG; }
+    *out = nullptr;
+    EPP_TRY(validate_csr(g));
+    if (L < 1) { epp_set_error("L must be >= 1 (got %d)", L); return EPP_ERR_INVALID_ARG; }
+    if (n_train < 0 || (n_train > 0 && !train_ids)) { epp_set_error("bad training set"); return EPP_ERR_INVALID_ARG; }
+    hipStream_t s = (hipStream_t)stream;
+    const int64_t n = g->n, nnz = g->nnz;
+    const int64_t n_words = (n + 63) / 64;
+    const int64_t n_seg = (nnz + 63) / 64;
+    const unsigned edge_tiles = grid_for(n_seg, kSegsPerTile);
+    const unsigned word_tiles = grid_for(n_words, kWordsPerTile);
+
+    HostScalars hs;
+    EPP_TRY(hs.init());
+    epp_paths* P = new epp_paths();
+    struct Guard { epp_paths* p; ~Guard() { delete p; } } guard{P};
+    P->L = L;
+    P->n = n;
+    P->bitmaps.resize(L + 1);
+    P->set_size.assign(L + 1, 0);
+    P->path.assign(L, nullptr);
+    for (int k = 0; k <= L; ++k) {
+        EPP_TRY(P->bitmaps[k].alloc((size_t)n_words * 8));
+        EPP_HIP_TRY(hipMemsetAsync(P->bitmaps[k].p, 0, P->bitmaps[k].bytes, s));
+    }
+
+    DevBuf mask, seg_base, tile_cnt, tile_base, newptr, dev_total, err;
+    EPP_TRY(mask.alloc((size_t)n_seg * 8));
+    EPP_TRY(seg_base.alloc((size_t)n_seg * 4));
+    const size_t max_tiles = std::max<size_t>(std::max(edge_tiles, word_tiles), 1);
+    EPP_TRY(tile_cnt.alloc(max_tiles * 4));
+    EPP_TRY(tile_base.alloc(max_tiles * 4));
+    EPP_TRY(newptr.alloc((size_t)(n + 1) * 4));
+    EPP_TRY(dev_total.alloc(sizeof(long long)));
+    EPP_TRY(err.alloc(sizeof(int)));
+    EPP_HIP_TRY(hipMemsetAsync(err.p, 0, sizeof(int), s));
+    EPP_HIP_TRY(hipMemsetAsync(newptr.p, 0, newptr.bytes, s));
+
+    // N^0 = V_t (Property 1)
+    if (n_train > 0) {
+        hipLaunchKernelGGL(k_mark_training, dim3(grid_for(n_train, kBlock)), dim3(kBlock), 0, s, train_ids, n_train, n,
+                           P->bitmaps[0].as<unsigned int>(), err.as<int>());
+        EPP_HIP_TRY(hipGetLastError());
+        int herr = 0;
+        EPP_HIP_TRY(hipMemcpyAsync(&herr, err.p, sizeof(int), hipMemcpyDeviceToHost, s));
+        EPP_HIP_TRY(hipStreamSynchronize(s));
+        if (herr) {
+            epp_set_error("training id outside [0, %lld)", (long long)n);
+            return EPP_ERR_OUT_OF_RANGE_ID;
+        }
+    }
+    EPP_TRY(compact_bitmap(P->bitmaps[0], n, nullptr, 0, nullptr, nullptr, &P->set_size[0], tile_cnt, tile_base,
+                           dev_total, hs, s));
+
+    for (int k = 0; k < L; ++k) {
+        const int l = L - 1 - k;  // rows N^{k+1} = N^{L-l}, sources N^k = N^{L-l-1}
+        epp_path* p = new epp_path();
+        P->path[l] = p;
+        p->n = n;
+        p->n_src = P->set_size[k];
+        long long kept = 0;
+        if (edge_tiles) {
+            hipLaunchKernelGGL(k_edge_mask, dim3(edge_tiles), dim3(kBlock), 0, s, g->col, nnz, n_seg,
+                               P->bitmaps[k].as<unsigned int>(), mask.as<unsigned long long>(), tile_cnt.as<int>());
+            hipLaunchKernelGGL(k_scan_counts, dim3(1), dim3(1024), 0, s, tile_cnt.as<int>(), tile_base.as<int>(),
+                               (int64_t)edge_tiles, dev_total.as<long long>());
+            EPP_HIP_TRY(hipGetLastError());
+            EPP_HIP_TRY(hipMemcpyAsync(hs.p, dev_total.p, sizeof(long long), hipMemcpyDeviceToHost, s));
+            EPP_HIP_TRY(hipStreamSynchronize(s));
+            kept = hs.p[0];
+        }
+        p->nnz = kept;
+        EPP_TRY(p->cv.alloc((size_t)kept * sizeof(int2)));
+        if (edge_tiles) {
+            hipLaunchKernelGGL(k_edge_extract, dim3(edge_tiles), dim3(kBlock), 0, s, g->col, g->val, n_seg,
+                               mask.as<unsigned long long>(), tile_base.as<int>(), seg_base.as<int>(),
+                               p->cv.as<int2>());
+            EPP_HIP_TRY(hipGetLastError());
+        }
+        if (n > 0) {
+            hipLaunchKernelGGL(k_row_flags, dim3(grid_for(n, kBlock)), dim3(kBlock), 0, s, g->rowptr, n, nnz,
+                               mask.as<unsigned long long>(), seg_base.as<int>(), (int)kept, newptr.as<int>(),
+                               P->bitmaps[k + 1].as<unsigned long long>());
+            EPP_HIP_TRY(hipGetLastError());
+        }
+        EPP_TRY(compact_bitmap(P->bitmaps[k + 1], n, newptr.as<int>(), (int)kept, &p->row_ids, &p->rowptr,
+                               &P->set_size[k + 1], tile_cnt, tile_base, dev_total, hs, s));
+        p->n_rows = P->set_size[k + 1];
+        EPP_TRY(epp_path_finish(p, s));
+    }
+    EPP_HIP_TRY(hipStreamSynchronize(s));
+    guard.p = nullptr;
+    *out = P;
+    return EPP_OK;
+}
+
+extern "C" int epp_prepare_full(const epp_csr_t* g, epp_stream_t stream, epp_path_t** out) {
+    if (!out) { epp_set_error("out is NULL"); return EPP_ERR_INVALID_ARG; }
+    *out = nullptr;
+    EPP_TRY(validate_csr(g));
+    hipStream_t s = (hipStream_t)stream;
+    epp_path* p = new epp_path();
+    struct Guard { epp_path* p; ~Guard() { delete p; } } guard{p};
+    p->n = g->n;
+    p->n_rows = g->n;
+    p->nnz = g->nnz;
+    p->n_src = g->n;
+    p->all_rows = true;
+    EPP_TRY(p->rowptr.alloc((size_t)(g->n + 1) * 4));
+    EPP_TRY(p->cv.alloc((size_t)g->nnz * sizeof(int2)));
+    EPP_HIP_TRY(hipMemcpyAsync(p->rowptr.p, g->rowptr, (size_t)(g->n + 1) * 4, hipMemcpyDeviceToDevice, s));
+    if (g->nnz > 0) {
+        hipLaunchKernelGGL(k_interleave, dim3(grid_for(g->nnz, kBlock)), dim3(kBlock), 0, s, g->col, g->val, g->nnz,
+                           p->cv.as<int2>());
+        EPP_HIP_TRY(hipGetLastError());
+    }
+    EPP_TRY(epp_path_finish(p, s));
+    guard.p = nullptr;
+    *out = p;
+    return EPP_OK;
+}
+
+extern "C" int epp_num_layers(const epp_paths_t* p) {
+    if (!p) { epp_set_error("paths is NULL"); return EPP_ERR_INVALID_ARG; }
+    return p->L;
+}
+
+extern "C" epp_path_t* epp_get_path(epp_paths_t* p, int l) {
+    if (!p || l < 0 || l >= p->L) { epp_set_error("no such layer"); return nullptr; }
+    return p->path[l];
+}
+
+extern "C" int epp_path_export(const epp_path_t* p, int32_t* row_ids, int32_t* rowptr, int32_t* col, float* val,
+                               epp_stream_t stream) {
+    if (!p) { epp_set_error("path is NULL"); return EPP_ERR_INVALID_ARG; }
+    hipStream_t s = (hipStream_t)stream;
+    if (row_ids && p->n_rows > 0) {
+        if (p->all_rows) {
+            hipLaunchKernelGGL(k_iota, dim3(grid_for(p->n_rows, kBlock)), dim3(kBlock), 0, s, row_ids, p->n_rows);
+        } else {
+            EPP_HIP_TRY(hipMemcpyAsync(row_ids, p->row_ids.p, (size_t)p->n_rows * 4, hipMemcpyDeviceToDevice, s));
+        }
+    }
+    if (rowptr) EPP_HIP_TRY(hipMemcpyAsync(rowptr, p->rowptr.p, (size_t)(p->n_rows + 1) * 4, hipMemcpyDeviceToDevice, s));
+    if ((col || val) && p->nnz > 0) {
+        hipLaunchKernelGGL(k_deinterleave, dim3(grid_for(p->nnz, kBlock)), dim3(kBlock), 0, s, p->cv.as<int2>(), p->nnz,
+                           col, val);
+    }
+    EPP_HIP_TRY(hipGetLastError());
+    EPP_HIP_TRY(hipStreamSynchronize(s));
+    return EPP_OK;
+}
+
+extern "C" int epp_active_set_export(const epp_paths_t* p, int k, int32_t* ids, int64_t* count, epp_stream_t stream) {
+    if (!p || !count) { epp_set_error("NULL argument"); return EPP_ERR_INVALID_ARG; }
+    if (k < 0 || k > p->L) { epp_set_error("k=%d outside [0, %d]", k, p->L); return EPP_ERR_INVALID_ARG; }
+    hipStream_t s = (hipStream_t)stream;
+    if (!ids) { *count = p->set_size[k]; return EPP_OK; }
+    if (*count < p->set_size[k]) {
+        epp_set_error("ids buffer holds %lld entries, need %lld", (long long)*count, (long long)p->set_size[k]);
+        return EPP_ERR_INVALID_ARG;
+    }
+    HostScalars hs;
+    EPP_TRY(hs.init());
+    DevBuf tile_cnt, tile_base, dev_total, tmp;
+    const size_t tiles = std::max<size_t>(grid_for((p->n + 63) / 64, kWordsPerTile), 1);
+    EPP_TRY(tile_cnt.alloc(tiles * 4));
+    EPP_TRY(tile_base.alloc(tiles * 4));
+    EPP_TRY(dev_total.alloc(sizeof(long long)));
+    int64_t c = 0;
+    EPP_TRY(compact_bitmap(p->bitmaps[k], p->n, nullptr, 0, &tmp, nullptr, &c, tile_cnt, tile_base, dev_total, hs, s));
+    if (c > 0) EPP_HIP_TRY(hipMemcpyAsync(ids, tmp.p, (size_t)c * 4, hipMemcpyDeviceToDevice, s));
+    EPP_HIP_TRY(hipStreamSynchronize(s));
+    *count = c;
+    return EPP_OK;
+}
+
+extern "C" void epp_destroy_paths(epp_paths_t* p) { delete p; }
+extern "C" void epp_destroy_path(epp_path_t* p) { delete p; }

@@ -1,0 +1,183 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Paths and active sets: bit-exact.  Gradients: |gpu - oracle| <= 1e-6 + 1e-5 |oracle|.
+"""
+from pathlib import Path
+
+import numpy as np
+import pytest
+import torch
+
+import graphgen
+import oracle
+
+pytestmark = [pytest.mark.gpu,
+              pytest.mark.skipif(not torch.cuda.is_available(), reason="needs a GPU")]
+
+if torch.cuda.is_available():
+    import paper_2204_02662_amd as epp
+    from _util import (assert_close, assert_paths_bit_exact, gpu_prepare, gpu_prepare_full, run_full, run_partial,
+                       dev)
+
+
+def oprep(g, train, L):
+    return oracle.prepare(g.n, g.rowptr, g.col, g.val, np.asarray(train, np.int32), L)
+
+
+def check_layers(g, train, L, widths, seed, gs_list=(0,)):
+    """Full comparison on a graph small enough for the oracle to do every row."""
+    sets_o, paths_o = oprep(g, train, L)
+    paths = gpu_prepare(g, train, L)
+    assert_paths_bit_exact(paths, sets_o, paths_o, L)
+    full = gpu_prepare_full(g)
+    for l in range(L):
+        F = widths[l]
+        src = sets_o[L - l - 1]
+        X = graphgen.normal_rows(g.n, F, src, seed + l)
+        want = oracle.path_aggregate(g.n, paths_o[l], X)
+        p = paths.path(l)
+        for gs in gs_list:
+            if gs:
+                p.set_group_size(F, gs)
+            got = run_partial(p, X)
+            assert_close(got, want, f"partial l={l} F={F} gs={gs}")
+            # rows outside the path are not touched; rows inside are overwritten
+            mark = run_partial(p, X, poison=123.0)
+            rows = sets_o[L - l].astype(bool)
+            assert np.all(mark[~rows] == 123.0)
+            assert_close(mark[rows], want[rows], f"partial overwrite l={l}")
+        # never reads rows outside the source set
+        Xp = X.copy()
+        Xp[src == 0] = np.nan
+        assert_close(run_partial(p, Xp), want, f"nan-poison l={l}")
+        # the all-active kernel gives the same matrix (Theorem 1) and writes every row
+        assert_close(run_full(full, X), oracle.full_aggregate(g.n, g.rowptr, g.col, g.val, X), f"full l={l}")
+    return paths
+
+
+def test_worked_example_on_gpu():
+    edges = [(0, 1), (1, 2), (1, 3), (1, 4), (2, 3), (3, 4)]
+    g = graphgen.csr_from_edges(5, edges, self_loops=False, normalise=False)
+    paths = check_layers(g, [2, 4], 2, [3, 5], 1)
+    row_ids, rowptr, col, _ = (t.cpu().tolist() for t in paths.path(1).export())
+    assert (row_ids, rowptr, col) == ([1, 3], [0, 2, 4], [2, 4, 2, 4])
+    row_ids, rowptr, col, _ = (t.cpu().tolist() for t in paths.path(0).export())
+    assert (row_ids, rowptr, col) == ([0, 1, 2, 3, 4], [0, 1, 2, 4, 5, 7], [1, 3, 1, 3, 1, 1, 3])
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_small_random_graphs(seed):
+    rng = np.random.default_rng(seed)
+    n = int(rng.integers(50, 400))
+    sym = bool(seed & 1)
+    edges = [(int(u), int(v)) for u, v in rng.integers(0, n, (4 * n, 2)) if u != v]
+    g = graphgen.csr_from_edges(n, edges, self_loops=bool(seed & 2), symmetric=sym, normalise=sym)
+    if not sym:
+        g.val[:] = rng.uniform(0.25, 2.0, g.nnz).astype(np.float32)
+    train = rng.choice(n, size=max(1, n // 10), replace=False)
+    check_layers(g, train, 3, [int(x) for x in rng.integers(1, 70, 3)], 50 + seed, gs_list=(0, 1, 3))
+
+
+@pytest.mark.parametrize("F", [1, 2, 3, 4, 7, 8, 16, 31, 32, 41, 47, 64, 100, 128, 130, 256, 300])
+def test_widths_on_skewed_graph(F):
+    """Several tiles, hubs that get split, a ragged tail, every vector shape."""
+    g = graphgen.random_graph("rmat", 5003, seed=21, raw_draws=90_000)
+    train = graphgen.training_set(g.n, 300, 22)
+    sets_o, paths_o = oprep(g, train, 2)
+    paths = gpu_prepare(g, train, 2)
+    for l in range(2):
+        X = graphgen.normal_rows(g.n, F, sets_o[2 - l - 1], 23 + l)
+        want = oracle.path_aggregate(g.n, paths_o[l], X)
+        p = paths.path(l)
+        for gs in (0, 16, 1 << 20):
+            p.set_group_size(F, gs)
+            assert_close(run_partial(p, X), want, f"F={F} l={l} gs={gs}")
+
+
+def test_group_size_invariance_and_group_counts():
+    g = graphgen.random_graph("chung_lu", 4000, seed=31, target_edges=40_000)
+    train = graphgen.training_set(g.n, 400, 32)
+    sets_o, paths_o = oprep(g, train, 2)
+    paths = gpu_prepare(g, train, 2)
+    F = 16
+    X = graphgen.normal_rows(g.n, F, sets_o[1], 33)
+    want = oracle.path_aggregate(g.n, paths_o[0], X)
+    p = paths.path(0)
+    lens = np.diff(paths_o[0].rowptr).astype(np.int64)
+    for gs in (1, 2, 3, 8, 64, 10 ** 6):
+        p.set_group_size(F, gs)
+        assert_close(run_partial(p, X), want, f"gs={gs}")
+        i = p.info()
+        # neighbour grouping: consecutive chunks of at most gs entries
+        assert i.group_size == gs and i.n_groups == int(np.sum(-(-lens // gs)))
+        assert i.n_split_rows == int(np.sum(lens > gs))
+    p.set_group_size(F, 0)
+    assert p.info().group_size == p.select_group_size(F) >= 1
+    for lanes in (4, 16, 64):
+        p.set_group_size(F, 0, lanes)
+        assert_close(run_partial(p, X), want, f"lanes={lanes}")
+
+
+def test_special_cases_on_gpu():
+    rng = np.random.default_rng(3)
+    n = 300
+    edges = [(int(u), int(v)) for u, v in rng.integers(0, n, (900, 2)) if u != v]
+    g = graphgen.csr_from_edges(n, edges, self_loops=False)
+    # V_t = V, duplicates, single vertex, isolated vertex
+    for train in (np.arange(n), [5, 5, 9, 5], [0], [int(np.flatnonzero(np.diff(g.rowptr) == 0)[0])]
+                  if (np.diff(g.rowptr) == 0).any() else [1]):
+        check_layers(g, train, 2, [4, 9], 40)
+    # V_t empty: all paths empty, aggregate is a no-op
+    paths = gpu_prepare(g, np.zeros(0, np.int32), 2)
+    sets_o, paths_o = oprep(g, [], 2)
+    assert_paths_bit_exact(paths, sets_o, paths_o, 2)
+    X = graphgen.normal_rows(n, 8, None, 1)
+    assert np.all(run_partial(paths.path(0), X, poison=5.0) == 5.0)
+    # graph without edges
+    g0 = graphgen.csr_from_edges(10, [], self_loops=False)
+    paths = gpu_prepare(g0, [1, 2], 2)
+    assert_paths_bit_exact(paths, *oprep(g0, [1, 2], 2), 2)
+    assert np.all(run_full(gpu_prepare_full(g0), graphgen.normal_rows(10, 4, None, 1)) == 0.0)
+
+
+def test_error_paths():
+    g = graphgen.csr_from_edges(10, [(0, 1), (1, 2)], self_loops=True)
+    with pytest.raises(epp.EppError) as e:
+        gpu_prepare(g, [10], 2)
+    assert e.value.code == epp.EPP_ERR_OUT_OF_RANGE_ID
+    with pytest.raises(epp.EppError) as e:
+        gpu_prepare(g, [-1], 2)
+    assert e.value.code == epp.EPP_ERR_OUT_OF_RANGE_ID
+    with pytest.raises(epp.EppError) as e:
+        gpu_prepare(g, [1], 0)
+    assert e.value.code == epp.EPP_ERR_INVALID_ARG
+    paths = gpu_prepare(g, [1], 1)
+    x = torch.zeros(10, 4, device=dev())
+    with pytest.raises(epp.EppError):
+        epp.epp_full_aggregate(paths.path(0), x, torch.zeros_like(x))  # not an all-active handle
+    with pytest.raises(epp.EppError):
+        epp.epp_backward_aggregate(paths.path(0), x, x)  # aliasing
+
+
+def test_run_to_run_determinism_of_unsplit_rows():
+    g = graphgen.random_graph("rmat", 20_000, seed=61, raw_draws=300_000)
+    train = graphgen.training_set(g.n, 2000, 62)
+    sets_o, paths_o = oprep(g, train, 2)
+    paths = gpu_prepare(g, train, 2)
+    F = 32
+    X = graphgen.normal_rows(g.n, F, sets_o[1], 63)
+    p = paths.path(0)
+    p.set_group_size(F, 64)
+    a, b, c = (run_partial(p, X) for _ in range(3))
+    lens = np.diff(paths_o[0].rowptr)
+    unsplit = paths_o[0].row_ids[lens <= 64]
+    assert np.array_equal(a[unsplit], b[unsplit]) and np.array_equal(a[unsplit], c[unsplit])
+    want = oracle.path_aggregate(g.n, paths_o[0], X)
+    for r in (a, b, c):
+        assert_close(r, want, "split rows")
+
+
+@pytest.mark.parametrize("k", [1, 2])
+def test_small_configs_every_entry(k):
+    cfg = graphgen.make_config(k)
+    check_layers(cfg.graph, cfg.train_ids, cfg.L, cfg.widths, cfg.seed(10))
