@@ -1,0 +1,254 @@
+#!/usr/bin/env python3
+"""Backward-aggregation benchmark on one MI355X.
+
+A "step" is one epoch of backward aggregation: one launch of the partially-active kernel
+per layer, l = L-1 ... 0 (Alg. 2), over synthetic inputs that are already resident in HBM.
+Prints ONE JSON line (see README for the fields).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from pathlib import Path
+
+ROOT = Path(__file__).resolve().parent
+if str(ROOT) not in sys.path:
+    sys.path.insert(0, str(ROOT))
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def log(*a):
+    print("[bench]", *a, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(R: int, S: int, nnz: int, F: int) -> int:
+    """Compulsory HBM bytes of one layer launch: the path's index arrays once (row ids,
+    row pointer, column ids, weights), every distinct source row once, every output row once."""
+    return 4 * (2 * R + 1) + 8 * nnz + 4 * F * S + 4 * F * R
+
+
+def edge_bytes(R: int, nnz: int, F: int) -> int:
+    """Bytes issued if no gathered row were ever reused: (8 + 4F) per entry + output."""
+    return 4 * (2 * R + 1) + 8 * nnz + 4 * F * nnz + 4 * F * R
+
+
+def read_traffic(workload: str):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter
+    summary (profiles/hbm_traffic.txt: lines `<workload> <layer> <fetch_bytes> <write_bytes>`)."""
+    f = ROOT / "profiles" / "hbm_traffic.txt"
+    out = {}
+    if f.exists():
+        for line in f.read_text().splitlines():
+            parts = line.split()
+            if len(parts) == 4 and parts[0] == workload:
+                out[int(parts[1])] = float(parts[2]) + float(parts[3])
+    return out
+
+
+def cpu_baseline(cfg, budget_s: float):
+    """The CPU oracle, as it stands, timed on this machine's host cores on a strided sample of
+    path rows of every layer; scaled to a whole epoch by the share of entries sampled."""
+    import numpy as np
+
+    import graphgen
+    import oracle
+
+    g, L = cfg.graph, cfg.L
+    threads = oracle.max_threads()
+    log(f"cpu_baseline: oracle path preparing on {threads} threads")
+    sets_o, paths_o = oracle.prepare(g.n, g.rowptr, g.col, g.val, cfg.train_ids, L)
+    work = [paths_o[l].col.size * cfg.widths[l] for l in range(L)]
+    total_work = float(sum(work))
+    est_ms, sampled_s, strides = 0.0, 0.0, []
+    for l in range(L - 1, -1, -1):
+        po, F = paths_o[l], cfg.widths[l]
+        X = graphgen.layer_gradient(cfg, l, sets_o[L - l - 1])
+        R = po.row_ids.size
+        if R == 0:
+            strides.append(1)
+            continue
+        # calibrate on a thin sample, then size the real sample to this layer's share of the budget
+        s0 = max(1, R // 2000)
+        t = time.perf_counter()
+        oracle.path_aggregate(g.n, po, X, first=0, stride=s0)
+        t_cal = max(time.perf_counter() - t, 1e-4)
+        lens = np.diff(po.rowptr)
+        frac_cal = lens[0::s0].sum() / max(po.col.size, 1)
+        full_est = t_cal / max(frac_cal, 1e-9)
+        share = budget_s * work[l] / total_work
+        stride = max(1, int(np.ceil(full_est / max(share, 1e-3))))
+        t = time.perf_counter()
+        oracle.path_aggregate(g.n, po, X, first=0, stride=stride)
+        dt = time.perf_counter() - t
+        frac = lens[0::stride].sum() / max(po.col.size, 1)
+        est_ms += dt / max(frac, 1e-12) * 1e3
+        sampled_s += dt
+        strides.append(stride)
+        del X
+    return {
+        "value": est_ms, "unit": "ms/epoch", "cores": threads, "kind": "oracle",
+        "sample": (f"every k-th path row of each layer (k={strides} for l=L-1..0), all widths; "
+                   f"{sampled_s:.1f} s of CPU work scaled by the share of entries sampled"),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=int(os.environ.get("EPP_BENCH_CONFIG", "5")))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-all-active", action="store_true")
+    ap.add_argument("--cpu-budget-s", type=float, default=15.0)
+    ap.add_argument("--layers", type=str, default="", help="comma list of layers to run (profiling); default all")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference point for the HBM byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (the path has no multi-GPU part); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import graphgen
+    import paper_2204_02662_amd as epp
+
+    epp.load_library()  # fails loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda", 0)
+
+    t0 = time.perf_counter()
+    cfg = graphgen.make_config(args.config)
+    g, L = cfg.graph, cfg.L
+    log(f"{cfg.name}: n={g.n} nnz={g.nnz} L={L} widths(l=0..)={cfg.widths} |V_t|={cfg.n_train} "
+        f"generated in {time.perf_counter() - t0:.1f}s")
+
+    rowptr, col, val = (torch.from_numpy(a).to(dev) for a in (g.rowptr, g.col, g.val))
+    train = torch.from_numpy(cfg.train_ids).to(dev)
+    torch.cuda.synchronize()
+    t = time.perf_counter()
+    paths = epp.epp_prepare(g.n, rowptr, col, val, train, L)
+    torch.cuda.synchronize()
+    prepare_ms = (time.perf_counter() - t) * 1e3
+    full = None if args.no_all_active else epp.epp_prepare_full(g.n, rowptr, col, val)
+
+    # inputs resident in HBM: N(0,1) on the source rows of each layer, zeros elsewhere
+    gen = torch.Generator(device=dev)
+    grad_in, grad_out, infos = [], [], []
+    for l in range(L):
+        F = cfg.widths[l]
+        src = paths.active_set(L - l - 1).long()
+        x = torch.zeros(g.n, F, dtype=torch.float32, device=dev)
+        gen.manual_seed(cfg.seed(10 + l))
+        x[src] = torch.randn(src.numel(), F, generator=gen, dtype=torch.float32, device=dev)
+        grad_in.append(x)
+        grad_out.append(torch.zeros(g.n, F, dtype=torch.float32, device=dev))
+    del rowptr, col, val
+
+    order = [l for l in range(L - 1, -1, -1) if not args.layers or str(l) in args.layers.split(",")]
+    if args.calibrate_copy:
+        a = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        b = torch.empty_like(a)
+        b.copy_(a)  # 1 GiB read + 1 GiB written by one elementwise kernel
+        torch.cuda.synchronize()
+        del a, b
+
+    path_objs = [paths.path(l) for l in range(L)]
+
+    def timed(run_layer, steps, warmup):
+        for _ in range(warmup):
+            for l in order:
+                run_layer(l)
+        torch.cuda.synchronize()
+        ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in order]
+              for _ in range(steps)]
+        t = time.perf_counter()
+        for s in range(steps):
+            for i, l in enumerate(order):
+                ev[s][i][0].record()
+                run_layer(l)
+                ev[s][i][1].record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t) * 1e3 / steps
+        per_layer = {l: float(np.mean([ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(steps)]))
+                     for i, l in enumerate(order)}
+        return wall_ms, per_layer
+
+    ms_partial, layer_ms = timed(lambda l: epp.epp_backward_aggregate(path_objs[l], grad_in[l], grad_out[l]),
+                                 args.steps, args.warmup)
+    for l in range(L):
+        infos.append(path_objs[l].info())
+
+    layers = []
+    for l in order:
+        i, F = infos[l], cfg.widths[l]
+        bmin, bedge = algorithmic_bytes(i.n_rows, i.n_src, i.nnz, F), edge_bytes(i.n_rows, i.nnz, F)
+        ms = layer_ms[l]
+        layers.append({
+            "l": l, "F": F, "rows": i.n_rows, "sources": i.n_src, "nnz": i.nnz, "max_len": i.max_len,
+            "group_size": i.group_size, "groups": i.n_groups, "split_rows": i.n_split_rows,
+            "ms": ms, "algorithmic_bytes": bmin, "roofline_GBs": bmin / ms / 1e6 if ms > 0 else None,
+            "roofline_frac": bmin / ms / 1e6 / HBM_PEAK_GBS if ms > 0 else None,
+            "gather_GBs": bedge / ms / 1e6 if ms > 0 else None,
+        })
+    dom = max(layers, key=lambda d: d["ms"])
+    traffic = read_traffic(cfg.name).get(dom["l"])
+    roofline = {
+        "bound": "hbm", "kernel": f"k_aggregate (layer l={dom['l']}, F={dom['F']})",
+        "achieved": dom["roofline_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": dom["roofline_frac"], "traffic": traffic,
+    }
+
+    result = {
+        "metric": "backward_aggregation_ms_per_epoch", "value": ms_partial, "unit": "ms/epoch",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_partial,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "n": g.n, "nnz": g.nnz, "undirected_edges": g.undirected_edges,
+                   "L": L, "widths_l0_first": cfg.widths, "n_train": cfg.n_train,
+                   "max_degree": int(np.diff(g.rowptr).max())},
+        "roofline": roofline,
+        "partially_active": {"ms_per_epoch": ms_partial, "sum_layer_ms": sum(layer_ms.values()), "layers": layers},
+        "prepare_ms": prepare_ms,
+        "path_bytes_over_csr_bytes": sum(i.bytes for i in infos) / (8.0 * g.nnz + 4.0 * (g.n + 1)),
+    }
+
+    if full is not None:
+        k_full = max(3, args.steps // 4)
+        ms_full, full_layer_ms = timed(lambda l: epp.epp_full_aggregate(full, grad_in[l], grad_out[l]), k_full,
+                                       min(args.warmup, 2))
+        fi = full.info()
+        fl = []
+        for l in order:
+            F = cfg.widths[l]
+            bmin = algorithmic_bytes(g.n, g.n, g.nnz, F)
+            fl.append({"l": l, "F": F, "ms": full_layer_ms[l], "algorithmic_bytes": bmin,
+                       "roofline_frac": bmin / full_layer_ms[l] / 1e6 / HBM_PEAK_GBS,
+                       "group_size": fi.group_size if fi.sched_F == F else None})
+        result["all_active"] = {"ms_per_epoch": ms_full, "steps": k_full, "layers": fl}
+        result["speedup_partial_over_all_active"] = ms_full / ms_partial if ms_partial > 0 else None
+        saved = ms_full - ms_partial
+        result["break_even_epochs"] = prepare_ms / saved if saved > 0 else None
+
+    if not args.no_cpu_baseline:
+        del grad_out
+        torch.cuda.empty_cache()
+        result["cpu_baseline"] = cpu_baseline(cfg, args.cpu_budget_s)
+    else:
+        result["cpu_baseline"] = None
+
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()
