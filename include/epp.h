@@ -56,9 +56,9 @@ typedef struct {
     int64_t bytes;        /* device bytes held by the path (canonical arrays + schedules)   */
     /* schedule most recently used / built (0 if none yet) */
     int32_t sched_F;        /* gradient width it was built for                              */
-    int32_t group_size;     /* gs: upper bound on entries per group (Sec. 2.2, Sec. 5)      */
-    int64_t n_groups;       /* sum over rows of ceil(len / gs) (rows of length 0 count 1)   */
-    int64_t n_split_rows;   /* rows cut into more than one group (written with atomics)     */
+    int32_t group_size;     /* gs: entries per group (Sec. 2.2, Sec. 5)                     */
+    int64_t n_groups;       /* ceil(nnz / gs)                                               */
+    int64_t n_split_rows;   /* rows cut by a group boundary (written back with atomics)     */
 } epp_path_info_t;
 
 /* Execution path preparing (Sec. 4): computes N^k for k = 0..L (Theorem 1) by backward
@@ -94,16 +94,16 @@ int epp_path_export(const epp_path_t* p, int32_t* row_ids, int32_t* rowptr, int3
  * only) must hold *count entries; count (host) receives |N^k|.  Synchronises the stream. */
 int epp_active_set_export(const epp_paths_t* p, int k, int32_t* ids, int64_t* count, epp_stream_t stream);
 
-/* Structure-aware group size (Sec. 5, re-derived for 64-lane wavefronts): the upper bound
- * gs on entries per group that this library picks for gradient width F from the path's
+/* Structure-aware group size (Sec. 5, re-derived for 64-lane wavefronts): the number gs of
+ * consecutive entries of the path's edge array that form one group (the scheduling unit of
+ * Sec. 2.2), as this library picks it for gradient width F from the path's size and
  * row-length histogram.  Pure function of (path, F); returns gs >= 1 or a negative error. */
 int epp_select_group_size(const epp_path_t* p, int F);
 
 /* Force the group size used for width F (sweeps, ablations); gs <= 0 restores the selector.
- * Rebuilds the group table (neighbour grouping, Sec. 2.2: each row is cut into consecutive
- * groups of at most gs entries).  lanes_per_row_hint: 0 = automatic; otherwise the maximal
- * number of lanes that cooperate on one group, a power of two <= 64.  Synchronises. */
-int epp_path_set_group_size(epp_path_t* p, int F, int gs, int lanes_per_row_hint, epp_stream_t stream);
+ * Rebuilds the group table: group g holds entries [g*gs, (g+1)*gs) of the edge array, so a
+ * row longer than gs is always cut and short rows share a group.  Synchronises. */
+int epp_path_set_group_size(epp_path_t* p, int F, int gs, epp_stream_t stream);
 
 /* Partially-active backward aggregation of one layer (Alg. 2, aggregation loop):
  *     grad_out[v, :] = sum over entries (u, e_vu) of row v in SG_l of  e_vu * grad_in[u, :]

@@ -69,7 +69,7 @@ def load_library() -> ctypes.CDLL:
     lib.epp_path_export.argtypes = [P, P, P, P, P, P]
     lib.epp_active_set_export.argtypes = [P, I, P, ctypes.POINTER(I64), P]
     lib.epp_select_group_size.argtypes = [P, I]
-    lib.epp_path_set_group_size.argtypes = [P, I, I, I, P]
+    lib.epp_path_set_group_size.argtypes = [P, I, I, P]
     lib.epp_backward_aggregate.argtypes = [P, P, P, I, P]
     lib.epp_full_aggregate.argtypes = [P, P, P, I, P]
     lib.epp_destroy_paths.argtypes = [P]
@@ -149,12 +149,12 @@ class Path_:
     def select_group_size(self, F: int) -> int:
         return _check(load_library().epp_select_group_size(self._h, F))
 
-    def set_group_size(self, F: int, gs: int, lanes_per_row_hint: int = 0) -> None:
-        _check(load_library().epp_path_set_group_size(self._h, F, gs, lanes_per_row_hint, _stream()))
+    def set_group_size(self, F: int, gs: int) -> None:
+        _check(load_library().epp_path_set_group_size(self._h, F, gs, _stream()))
 
     def __del__(self):
-        if getattr(self, "_owned", False) and self._h:
-            load_library().epp_destroy_path(self._h)
+        if getattr(self, "_owned", False) and self._h and _lib is not None:
+            _lib.epp_destroy_path(self._h)
             self._h = None
 
 
@@ -184,8 +184,8 @@ class Paths:
         return ids
 
     def __del__(self):
-        if getattr(self, "_h", None):
-            load_library().epp_destroy_paths(self._h)
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.epp_destroy_paths(self._h)
             self._h = None
 
 

@@ -1,15 +1,24 @@
 // Gather-reduce SpMM of backward aggregation (Alg. 1 / Alg. 2 aggregation loops) for
 // gfx950, and the neighbour-group schedule it runs on (Sec. 2.2, Sec. 5).
 //
-// Work decomposition (wave64):
-//   * a source row of F floats is read by T lanes, VEC floats each (T*VEC >= F when it fits);
-//   * a group (<= gs consecutive entries of one destination row) is processed by E "slots"
-//     of T lanes; slot k takes entries k, k+E, k+2E, ...; partial sums meet through
-//     cross-lane shuffles;
-//   * a wavefront therefore carries 64/(T*E) groups at once.  Groups are binned by length
-//     class, and E is chosen per class, so the groups of one wavefront have similar lengths.
-//   * rows longer than gs are cut into several groups, whose partial sums are added to the
-//     (pre-zeroed) output row with hardware fp32 atomics; all other rows use plain stores.
+// Neighbour grouping, re-derived for 64-lane wavefronts.  The path's entry array (the
+// concatenated filtered neighbour lists, rows in ascending order) is cut into groups of gs
+// consecutive entries.  A group is the scheduling unit, as in Sec. 2.2, but it is a slice
+// of the *edge array*, not of one row: a long row is cut into several groups, and many
+// short rows share one group.  Every group costs the same number of gathers, so
+// wavefronts stay busy equally long whatever the degree distribution looks like.
+//
+// Execution (wave64):
+//   * a source row of F floats is read by T lanes, VEC floats each (T*VEC >= F if it fits);
+//     such a set of T lanes is a "slot" and owns one group: a wavefront carries 64/T groups;
+//   * the slot streams its group's (column, weight) pairs U at a time, issues the U row
+//     gathers back to back, and prefetches the next U pairs while they are in flight;
+//   * the last entry of every row carries a flag (sign bit of the column id).  When a slot
+//     meets it, the accumulated row is written: with a plain store if the whole row lies
+//     inside the group, with hardware fp32 atomics if the row is shared with a neighbouring
+//     group (rows cut by a group boundary are zeroed by a small kernel first);
+//   * no cross-lane reduction is needed: lanes split the feature dimension, never a row's
+//     neighbours, so the only cross-group combination is the atomic write-back.
 
 #include <algorithm>
 #include <cstdlib>
@@ -20,190 +29,191 @@
 namespace {
 
 constexpr int kBlock = 256;
+constexpr int kRowEnd = (int)0x80000000u;
 
-struct ClassTab {
-    int n_used;
-    int n_waves;
-    int wave_begin[EPP_NCLASS + 1];  // first wavefront of the k-th used class
-    int group_begin[EPP_NCLASS];     // first group of that class in the group arrays
-    int group_count[EPP_NCLASS];
-    int log2E[EPP_NCLASS];           // slots per group
-};
-
-__device__ __forceinline__ int length_class(int len) { return len <= 1 ? 0 : 32 - __clz(len - 1); }
+typedef int int2v __attribute__((ext_vector_type(2)));
+typedef float float2v __attribute__((ext_vector_type(2)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+template <int VEC> struct VecT;
+template <> struct VecT<1> { typedef float type; };
+template <> struct VecT<2> { typedef float2v type; };
+template <> struct VecT<4> { typedef float4v type; };
+template <int VEC> __device__ __forceinline__ float lane_get(const typename VecT<VEC>::type& x, int i) { return x[i]; }
+template <> __device__ __forceinline__ float lane_get<1>(const float& x, int) { return x; }
 
 // ---------------------------------------------------------------- schedule construction
-// counts[c] = groups of class c; counts[32] = rows cut into more than one group.
-__global__ __launch_bounds__(kBlock) void k_sched_count(const int32_t* __restrict__ rowptr, int64_t n_rows, int gs,
-                                                        unsigned long long* __restrict__ counts) {
-    __shared__ int h[EPP_NCLASS + 1];
-    if (threadIdx.x <= EPP_NCLASS) h[threadIdx.x] = 0;
-    __syncthreads();
-    int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (r < n_rows) {
-        int len = rowptr[r + 1] - rowptr[r];
-        if (len <= gs) {
-            atomicAdd(&h[length_class(len)], 1);
-        } else {
-            int q = len / gs, rem = len - q * gs;
-            atomicAdd(&h[length_class(gs)], q);
-            if (rem) atomicAdd(&h[length_class(rem)], 1);
-            atomicAdd(&h[EPP_NCLASS], 1);
-        }
+// One thread per group: the row that holds the group's first entry (search in the row
+// pointer; streamed rows are non-empty, so the pointer is strictly increasing).  Bit 31
+// marks a group that starts inside a row.  A row cut by group boundaries is appended to
+// cut_rows once, by the first boundary inside it.
+__global__ __launch_bounds__(kBlock) void k_sched_groups(const int32_t* __restrict__ rowptr, int64_t n_rows, int gs,
+                                                         int64_t n_groups, int32_t* __restrict__ group_row,
+                                                         int32_t* __restrict__ cut_rows,
+                                                         unsigned int* __restrict__ n_cut) {
+    int64_t g = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (g >= n_groups) return;
+    const int64_t first = g * gs;
+    int64_t lo = 0, hi = n_rows - 1;  // largest r with rowptr[r] <= first
+    while (lo < hi) {
+        int64_t mid = (lo + hi + 1) >> 1;
+        if (rowptr[mid] <= first) lo = mid; else hi = mid - 1;
     }
-    __syncthreads();
-    if (threadIdx.x <= EPP_NCLASS && h[threadIdx.x])
-        atomicAdd(&counts[threadIdx.x], (unsigned long long)h[threadIdx.x]);
-}
-
-// cursor[c] starts at the first slot of class c (cursor[32] at 0 for the split-row list).
-__global__ __launch_bounds__(kBlock) void k_sched_fill(const int32_t* __restrict__ rowptr,
-                                                       const int32_t* __restrict__ row_ids, int64_t n_rows, int gs,
-                                                       unsigned int* __restrict__ cursor, int32_t* __restrict__ g_start,
-                                                       int32_t* __restrict__ g_len, int32_t* __restrict__ g_dst,
-                                                       int32_t* __restrict__ split_dst) {
-    __shared__ int h[EPP_NCLASS + 1];
-    __shared__ unsigned int base[EPP_NCLASS + 1];
-    if (threadIdx.x <= EPP_NCLASS) h[threadIdx.x] = 0;
-    __syncthreads();
-    int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    int start = 0, len = 0, q = 0, rem = 0, cq = 0, cr = 0, rank_q = 0, rank_r = 0, rank_s = 0;
-    bool split = false, have = r < n_rows;
-    if (have) {
-        start = rowptr[r];
-        len = rowptr[r + 1] - start;
-        if (len <= gs) {
-            rem = len;
-            cr = length_class(len);
-            rank_r = atomicAdd(&h[cr], 1);
-        } else {
-            split = true;
-            q = len / gs;
-            rem = len - q * gs;
-            cq = length_class(gs);
-            rank_q = atomicAdd(&h[cq], q);
-            if (rem) { cr = length_class(rem); rank_r = atomicAdd(&h[cr], 1); }
-            rank_s = atomicAdd(&h[EPP_NCLASS], 1);
-        }
-    }
-    __syncthreads();
-    if (threadIdx.x <= EPP_NCLASS && h[threadIdx.x])
-        base[threadIdx.x] = atomicAdd(&cursor[threadIdx.x], (unsigned int)h[threadIdx.x]);
-    __syncthreads();
-    if (!have) return;
-    const int32_t dst = row_ids ? row_ids[r] : (int32_t)r;
-    const int flag = split ? (int)0x80000000u : 0;
-    for (int i = 0; i < q; ++i) {
-        unsigned int g = base[cq] + rank_q + i;
-        g_start[g] = start + i * gs;
-        g_len[g] = gs | flag;
-        g_dst[g] = dst;
-    }
-    if (!split || rem) {
-        unsigned int g = base[cr] + rank_r;
-        g_start[g] = start + q * gs;
-        g_len[g] = rem | flag;
-        g_dst[g] = dst;
-    }
-    if (split) split_dst[base[EPP_NCLASS] + rank_s] = dst;
+    const int64_t start = rowptr[lo];
+    const bool inside = start < first;
+    group_row[g] = (int32_t)lo | (inside ? kRowEnd : 0);
+    if (inside && start >= first - gs) cut_rows[atomicAdd(n_cut, 1u)] = (int32_t)lo;
 }
 
 // ------------------------------------------------------------------------- aggregation
-__global__ __launch_bounds__(kBlock) void k_zero_rows(const int32_t* __restrict__ rows, int64_t n_rows, int F,
+// Zero the rows that receive atomics (rows cut by a group boundary, given as streamed-row
+// indices) or, for the all-active graph, the vertices whose lists are empty.
+__global__ __launch_bounds__(kBlock) void k_zero_rows(const int32_t* __restrict__ rows, int64_t n_rows,
+                                                      const int32_t* __restrict__ row_ids, int F,
                                                       float* __restrict__ out) {
     int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (i >= n_rows * F) return;
     int64_t r = i / F;
     int f = (int)(i - r * F);
-    out[(size_t)rows[r] * F + f] = 0.0f;
+    int32_t v = rows[r];
+    if (row_ids) v = row_ids[v];
+    out[(size_t)v * F + f] = 0.0f;
 }
 
-template <int VEC> struct Vec;
-template <> struct Vec<1> { float v[1]; };
-template <> struct alignas(8) Vec<2> { float v[2]; };
-template <> struct alignas(16) Vec<4> { float v[4]; };
+struct AggArgs {
+    const int2v* cv;           // (column | row-end flag, weight bits) per entry
+    const int32_t* group_row;  // per group: first row (bit 31: starts inside that row)
+    const int32_t* row_ids;    // streamed row -> vertex; NULL: identity
+    const float* in;
+    float* out;
+    int64_t nnz;
+    int64_t n_groups;
+    int F;
+    int gs;
+    int log2ns;                // feature slices spread over the XCDs (1 << log2ns of them)
+};
 
-// VEC floats per lane, T lanes per source row, U gathers in flight per lane.
-template <int VEC, int LOG2T, int U>
-__global__ __launch_bounds__(kBlock) void k_aggregate(const int2* __restrict__ cv, const int32_t* __restrict__ g_start,
-                                                      const int32_t* __restrict__ g_len,
-                                                      const int32_t* __restrict__ g_dst, const float* __restrict__ in,
-                                                      float* __restrict__ out, int F, ClassTab tab) {
-    constexpr int T = 1 << LOG2T;
-    const int lane = threadIdx.x & 63;
-    const int wave = blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
-    if (wave >= tab.n_waves) return;
-    int k = 0;
-    while (k + 1 < tab.n_used && wave >= tab.wave_begin[k + 1]) ++k;
-    const int log2E = tab.log2E[k];
-    const int E = 1 << log2E;
-    const int log2W = LOG2T + log2E;
-    const int sub = lane >> log2W;                // which group of this wavefront
-    const int slot = (lane >> LOG2T) & (E - 1);   // which slot of the group
-    const int t = lane & (T - 1);                 // which fragment of the row
-    const int gi = ((wave - tab.wave_begin[k]) << (6 - log2W)) + sub;
-    int start = 0, len = 0, dst = 0;
-    bool split = false;
-    const bool has = gi < tab.group_count[k];
-    if (has) {
-        const int g = tab.group_begin[k] + gi;
-        start = g_start[g];
-        const int lf = g_len[g];
-        len = lf & 0x7FFFFFFF;
-        split = lf < 0;
-        dst = g_dst[g];
+template <int VEC>
+__device__ __forceinline__ void write_row(float* __restrict__ o, const float (&acc)[VEC], bool atomic) {
+    if (atomic) {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) unsafeAtomicAdd(o + i, acc[i]);
+    } else {
+        typename VecT<VEC>::type r;
+        if constexpr (VEC == 1) {
+            r = acc[0];
+        } else {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) r[i] = acc[i];
+        }
+        __builtin_nontemporal_store(r, reinterpret_cast<typename VecT<VEC>::type*>(o));
     }
-    const int2* __restrict__ my = cv + start;
-    for (int f0 = 0; f0 < F; f0 += T * VEC) {
-        const int f = f0 + t * VEC;
-        const bool fok = f < F;
-        const float* __restrict__ src = in + f;
+}
+
+// VEC floats per lane, T = 2^LOG2T lanes per source row, U gathers in flight per lane.
+//
+// The (column, weight) pairs of a group are staged through LDS: the T lanes of a slot load
+// 4T consecutive pairs with four coalesced 8-byte loads, so every 128-byte line of the edge
+// array is fetched once and fully used even when T is small and the 64/T groups of the
+// wavefront lie far apart; each lane then reads the pair it needs as an LDS broadcast.
+// The next 4T pairs are fetched into registers while the current ones are consumed.  The
+// staging area is private to the wavefront (LDS operations of one wavefront execute in
+// order), so no workgroup barrier is involved.
+template <int VEC, int LOG2T, int U_>
+__global__ __launch_bounds__(kBlock) void k_aggregate(AggArgs a) {
+    constexpr int T = 1 << LOG2T;
+    constexpr int S = 4 * T;              // pairs staged per slot
+    constexpr int U = U_ < S ? U_ : S;    // S is a multiple of U
+    typedef typename VecT<VEC>::type vec_t;
+    __shared__ int2v stage_all[kBlock / 64][64 * 4];
+    int2v* __restrict__ stage = stage_all[threadIdx.x >> 6] + (((threadIdx.x & 63) >> LOG2T) * S);
+
+    // XCD-aware mapping.  Workgroups are dealt round-robin to the 8 XCDs (each with its own
+    // L2).  With ns > 1 feature slices, XCD x works on slice x % ns of every row only, so its
+    // L2 holds ns times as many distinct source rows; the 8/ns XCDs of a slice share the
+    // groups.  (A different dispatch order would cost locality, never correctness.)
+    const int ns = 1 << a.log2ns;
+    const int xcd = blockIdx.x & 7;
+    const int slice = xcd & (ns - 1);
+    const int64_t qb = ((int64_t)(blockIdx.x >> 3) << (3 - a.log2ns)) + (xcd >> a.log2ns);
+    const int64_t g = qb * (kBlock >> LOG2T) + (threadIdx.x >> LOG2T);
+    const bool has = g < a.n_groups;  // slots past the end idle through the loop (no early exit: LDS order)
+    const int t = threadIdx.x & (T - 1);
+    const int64_t j0 = has ? g * a.gs : 0;
+    const int len = has ? (int)(std::min<int64_t>(j0 + a.gs, a.nnz) - j0) : 0;
+    const int2v* __restrict__ my = a.cv + j0;
+    const int gr = has ? a.group_row[g] : 0;
+
+    for (int f0 = 0; f0 < a.F; f0 += (T * VEC) << a.log2ns) {
+        const int f = f0 + (slice * T + t) * VEC;
+        const bool fok = f < a.F;
+        const float* __restrict__ src = a.in + (fok ? f : 0);
+        float* __restrict__ dstbase = a.out + f;
+        int r = gr & 0x7FFFFFFF;
+        bool shared = gr < 0;  // the current row is shared with the previous group
+        int32_t v = (a.row_ids && has) ? a.row_ids[r] : r;
         float acc[VEC];
 #pragma unroll
         for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
-        if (fok) {
-            for (int j = slot; j < len; j += U << log2E) {
-                int2 e[U];
-                Vec<VEC> x[U];
+        bool open = false;  // acc holds entries of a row whose end has not been met
+
+        int2v pre[4];
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int jj = j + (u << log2E);
-                    e[u] = jj < len ? my[jj] : make_int2(-1, 0);
+        for (int i = 0; i < 4; ++i) {
+            const int j = i * T + t;
+            pre[i] = len > 0 ? __builtin_nontemporal_load(my + std::min(j, len - 1)) : int2v{0, 0};
+            if (j >= len) { pre[i].x &= 0x7FFFFFFF; pre[i].y = 0; }
+        }
+        for (int base = 0; base < len; base += S) {
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int i = 0; i < 4; ++i) stage[i * T + t] = pre[i];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            if (base + S < len) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int j = base + S + i * T + t;
+                    pre[i] = __builtin_nontemporal_load(my + std::min(j, len - 1));
+                    if (j >= len) { pre[i].x &= 0x7FFFFFFF; pre[i].y = 0; }
                 }
+            }
+            const int n_here = std::min(S, len - base);
+            for (int b = 0; b < n_here; b += U) {
+                // U independent row reads back to back, then U multiply-adds
+                int2v e[U];
+                vec_t x[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) e[u] = stage[b + u];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    if (e[u].x >= 0) {
-                        x[u] = *reinterpret_cast<const Vec<VEC>*>(src + (size_t)e[u].x * (size_t)F);
+                    if (fok) {
+                        x[u] = *reinterpret_cast<const vec_t*>(src + (size_t)(e[u].x & 0x7FFFFFFF) * (size_t)a.F);
                     } else {
-#pragma unroll
-                        for (int i = 0; i < VEC; ++i) x[u].v[i] = 0.0f;
+                        x[u] = vec_t{};
                     }
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const float w = __int_as_float(e[u].y);
 #pragma unroll
-                    for (int i = 0; i < VEC; ++i) acc[i] = fmaf(w, x[u].v[i], acc[i]);
+                    for (int i = 0; i < VEC; ++i) acc[i] = fmaf(w, lane_get<VEC>(x[u], i), acc[i]);
+                    const int j = base + b + u;
+                    if (j < len) open = true;
+                    if (e[u].x < 0) {  // last entry of row r
+                        if (fok) write_row<VEC>(dstbase + (size_t)v * (size_t)a.F, acc, shared);
+#pragma unroll
+                        for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
+                        shared = false;
+                        open = false;
+                        ++r;
+                        // vertex of the next row; the very last entry of the path has no successor
+                        if (!a.row_ids) v = r; else if (j0 + j + 1 < a.nnz) v = a.row_ids[r];
+                    }
                 }
             }
         }
-        // partial sums of the E slots meet in every slot
-        for (int s = T; s < (T << log2E); s <<= 1) {
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) acc[i] += __shfl_xor(acc[i], s, 64);
-        }
-        if (has && slot == 0 && fok) {
-            float* __restrict__ o = out + (size_t)dst * (size_t)F + f;
-            if (split) {
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) unsafeAtomicAdd(o + i, acc[i]);
-            } else {
-                Vec<VEC> r;
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) r.v[i] = acc[i];
-                *reinterpret_cast<Vec<VEC>*>(o) = r;
-            }
-        }
+        // the group ends inside a row: that row continues in the next group
+        if (open && fok) write_row<VEC>(dstbase + (size_t)v * (size_t)a.F, acc, true);
     }
 }
 
@@ -227,86 +237,89 @@ void row_shape(int F, int* vec, int* log2T) {
     *log2T = lt;
 }
 
-template <int VEC, int LOG2T>
-void launch_one(unsigned blocks, hipStream_t s, const epp_path* p, const Schedule* sc, const float* in, float* out, int F,
-                const ClassTab& tab) {
-    hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, 8>), dim3(blocks), dim3(kBlock), 0, s, p->cv.as<int2>(),
-                       sc->g_start.as<int32_t>(), sc->g_len.as<int32_t>(), sc->g_dst.as<int32_t>(), in, out, F, tab);
+template <int VEC, int LOG2T, int U>
+void launch_one(hipStream_t s, const AggArgs& a) {
+    const int64_t per_block = kBlock >> LOG2T;
+    const int64_t blocks_per_slice = (a.n_groups + per_block - 1) / per_block;
+    const int64_t xcds_per_slice = 8 >> a.log2ns;
+    const int64_t q = (blocks_per_slice + xcds_per_slice - 1) / xcds_per_slice;
+    hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U>), dim3((unsigned)(q * 8)), dim3(kBlock), 0, s, a);
 }
 
-template <int VEC>
-void launch_vec(int log2T, unsigned blocks, hipStream_t s, const epp_path* p, const Schedule* sc, const float* in,
-                float* out, int F, const ClassTab& tab) {
+template <int VEC, int U>
+void launch_vec(int log2T, hipStream_t s, const AggArgs& a) {
     switch (log2T) {
-        case 0: launch_one<VEC, 0>(blocks, s, p, sc, in, out, F, tab); break;
-        case 1: launch_one<VEC, 1>(blocks, s, p, sc, in, out, F, tab); break;
-        case 2: launch_one<VEC, 2>(blocks, s, p, sc, in, out, F, tab); break;
-        case 3: launch_one<VEC, 3>(blocks, s, p, sc, in, out, F, tab); break;
-        case 4: launch_one<VEC, 4>(blocks, s, p, sc, in, out, F, tab); break;
-        case 5: launch_one<VEC, 5>(blocks, s, p, sc, in, out, F, tab); break;
-        default: launch_one<VEC, 6>(blocks, s, p, sc, in, out, F, tab); break;
+        case 0: launch_one<VEC, 0, U>(s, a); break;
+        case 1: launch_one<VEC, 1, U>(s, a); break;
+        case 2: launch_one<VEC, 2, U>(s, a); break;
+        case 3: launch_one<VEC, 3, U>(s, a); break;
+        case 4: launch_one<VEC, 4, U>(s, a); break;
+        case 5: launch_one<VEC, 5, U>(s, a); break;
+        default: launch_one<VEC, 6, U>(s, a); break;
+    }
+}
+
+template <int U>
+void launch_u(int vec, int log2T, hipStream_t s, const AggArgs& a) {
+    switch (vec) {
+        case 4: launch_vec<4, U>(log2T, s, a); break;
+        case 2: launch_vec<2, U>(log2T, s, a); break;
+        default: launch_vec<1, U>(log2T, s, a); break;
     }
 }
 
 }  // namespace
 
-// Upper bound on entries per group for width F.  A group is worked on by at most 64/T
-// slots; the bound keeps every slot to a few dozen gathers so that long rows spread over
-// many wavefronts, while staying large enough that the atomic write-back of a split row
-// (F atomics per group) is a small fraction of the F * gs floats the group gathers.
+int epp_unroll() {
+    int u = env_int("EPP_TUNE_UNROLL", 8);
+    return u <= 4 ? 4 : (u >= 16 ? 16 : 8);
+}
+
+// Structure-aware group size (Sec. 5) re-derived for 64-lane wavefronts.
+//
+// On this machine a group is a fixed-cost unit (gs gathers of one row fragment each), so
+// load balance no longer depends on the degree distribution; what the group size trades is
+// (a) atomic write-back and zeroing of the rows cut by group boundaries, which falls as gs
+// grows, against (b) having enough groups to fill every slot of the GPU several times
+// over, which matters for small paths.  The slots of the GPU are
+//     256 CUs x 16 resident wavefronts x 64/T groups per wavefront,
+// with T the lanes one row of width F needs; the selector aims at about four rounds of
+// groups per slot and clamps gs to [16, 2048] (measured flat beyond 2048).
 int epp_default_group_size(const epp_path* p, int F) {
+    int forced = env_int("EPP_TUNE_GS", 0);
+    if (forced > 0) return forced;
     int vec, log2T;
     row_shape(F, &vec, &log2T);
-    const int slots = 64 >> log2T;
-    const int iters = env_int("EPP_TUNE_GROUP_ITERS", 64);
-    int64_t gs = (int64_t)slots * iters;
-    gs = std::max<int64_t>(gs, 64);
-    (void)p;
-    return (int)std::min<int64_t>(gs, 1 << 20);
+    const int64_t slots = 256ll * 16 * (64 >> log2T);
+    const int64_t want = p->nnz / (slots * 4);
+    int gs = 16;
+    while (gs * 2 <= want && gs < 2048) gs *= 2;
+    return gs;
 }
 
 int epp_build_schedule(epp_path* p, int gs, hipStream_t s, Schedule** out) {
     Schedule* sc = new Schedule();
     struct Guard { Schedule* s; ~Guard() { delete s; } } guard{sc};
     sc->gs = gs;
-    DevBuf counts;
-    EPP_TRY(counts.alloc((EPP_NCLASS + 1) * sizeof(unsigned long long)));
-    EPP_HIP_TRY(hipMemsetAsync(counts.p, 0, counts.bytes, s));
-    const unsigned blocks = (unsigned)((p->n_rows + kBlock - 1) / kBlock);
-    unsigned long long host[EPP_NCLASS + 1] = {};
-    if (blocks) {
-        hipLaunchKernelGGL(k_sched_count, dim3(blocks), dim3(kBlock), 0, s, p->rowptr.as<int32_t>(), p->n_rows, gs,
-                           counts.as<unsigned long long>());
+    sc->unroll = epp_unroll();
+    sc->log2_slices = env_int("EPP_TUNE_LOG2_SLICES", 0);
+    const int64_t n_groups = (p->nnz + gs - 1) / gs;
+    if (n_groups >= 0x7FFFFFFFll) { epp_set_error("too many groups"); return EPP_ERR_TOO_LARGE; }
+    sc->n_groups = n_groups;
+    EPP_TRY(sc->group_row.alloc((size_t)n_groups * 4));
+    EPP_TRY(sc->cut_rows.alloc((size_t)n_groups * 4));
+    if (n_groups > 0) {
+        DevBuf cnt;
+        EPP_TRY(cnt.alloc(sizeof(unsigned int)));
+        EPP_HIP_TRY(hipMemsetAsync(cnt.p, 0, sizeof(unsigned int), s));
+        hipLaunchKernelGGL(k_sched_groups, dim3((unsigned)((n_groups + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
+                           p->rowptr.as<int32_t>(), p->n_stream_rows, gs, n_groups, sc->group_row.as<int32_t>(),
+                           sc->cut_rows.as<int32_t>(), cnt.as<unsigned int>());
         EPP_HIP_TRY(hipGetLastError());
-        EPP_HIP_TRY(hipMemcpyAsync(host, counts.p, sizeof(host), hipMemcpyDeviceToHost, s));
+        unsigned int h = 0;
+        EPP_HIP_TRY(hipMemcpyAsync(&h, cnt.p, sizeof(h), hipMemcpyDeviceToHost, s));
         EPP_HIP_TRY(hipStreamSynchronize(s));
-    }
-    // longest classes first: the long groups start early and the short ones fill the tail
-    int64_t total = 0;
-    unsigned int cursor[EPP_NCLASS + 1] = {};
-    for (int c = EPP_NCLASS - 1; c >= 0; --c) {
-        sc->class_count[c] = (int64_t)host[c];
-        sc->class_begin[c] = total;
-        cursor[c] = (unsigned int)total;
-        total += (int64_t)host[c];
-    }
-    if (total >= 0x7FFFFFFFll) { epp_set_error("too many groups"); return EPP_ERR_TOO_LARGE; }
-    sc->n_groups = total;
-    sc->n_split_rows = (int64_t)host[EPP_NCLASS];
-    EPP_TRY(sc->g_start.alloc((size_t)total * 4));
-    EPP_TRY(sc->g_len.alloc((size_t)total * 4));
-    EPP_TRY(sc->g_dst.alloc((size_t)total * 4));
-    EPP_TRY(sc->split_dst.alloc((size_t)sc->n_split_rows * 4));
-    if (blocks) {
-        DevBuf cur;
-        EPP_TRY(cur.alloc(sizeof(cursor)));
-        EPP_HIP_TRY(hipMemcpyAsync(cur.p, cursor, sizeof(cursor), hipMemcpyHostToDevice, s));
-        hipLaunchKernelGGL(k_sched_fill, dim3(blocks), dim3(kBlock), 0, s, p->rowptr.as<int32_t>(),
-                           p->all_rows ? nullptr : p->row_ids.as<int32_t>(), p->n_rows, gs, cur.as<unsigned int>(),
-                           sc->g_start.as<int32_t>(), sc->g_len.as<int32_t>(), sc->g_dst.as<int32_t>(),
-                           sc->split_dst.as<int32_t>());
-        EPP_HIP_TRY(hipGetLastError());
-        EPP_HIP_TRY(hipStreamSynchronize(s));
+        sc->n_split_rows = h;
     }
     guard.s = nullptr;
     p->scheds.push_back(sc);
@@ -314,48 +327,47 @@ int epp_build_schedule(epp_path* p, int gs, hipStream_t s, Schedule** out) {
     return EPP_OK;
 }
 
-int epp_launch_aggregate(epp_path* p, Schedule* sc, int lanes_hint, const float* in, float* out, int F,
-                         hipStream_t s) {
-    if (sc->n_groups == 0) return EPP_OK;
+int epp_launch_aggregate(epp_path* p, Schedule* sc, const float* in, float* out, int F, hipStream_t s) {
     int vec, log2T;
     row_shape(F, &vec, &log2T);
     if (vec > 1 && ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & (uintptr_t)(vec * 4 - 1))) {
         vec = 1;  // base pointers not aligned for vector access
         log2T = std::min(ceil_log2(F), 6);
     }
-    const int max_log2E = std::min(6 - log2T, lanes_hint > 0 ? std::max(ceil_log2(lanes_hint) - log2T, 0) : 6);
-    const int slot_iters = std::max(env_int("EPP_TUNE_SLOT_ITERS", 8), 1);
-
-    ClassTab tab;
-    std::memset(&tab, 0, sizeof(tab));
-    int64_t waves = 0;
-    for (int c = EPP_NCLASS - 1; c >= 0; --c) {
-        if (sc->class_count[c] == 0) continue;
-        // class c holds lengths up to 2^c: widen until a slot has about slot_iters entries
-        int want = c - ceil_log2(slot_iters);
-        int log2E = std::min(std::max(want, 0), max_log2E);
-        int groups_per_wave = 64 >> (log2T + log2E);
-        int k = tab.n_used++;
-        tab.wave_begin[k] = (int)waves;
-        tab.group_begin[k] = (int)sc->class_begin[c];
-        tab.group_count[k] = (int)sc->class_count[c];
-        tab.log2E[k] = log2E;
-        waves += (sc->class_count[c] + groups_per_wave - 1) / groups_per_wave;
-    }
-    if (waves >= 0x7FFFFFFFll) { epp_set_error("too many wavefronts"); return EPP_ERR_TOO_LARGE; }
-    tab.wave_begin[tab.n_used] = (int)waves;
-    tab.n_waves = (int)waves;
-
+    // feature slices over the XCDs: each slice keeps whole 128-byte lines of a row
+    int log2ns = std::min(std::max(sc->log2_slices, 0), 3);
+    while (log2ns > 0 && ((log2T - log2ns) < 0 || ((vec * 4) << (log2T - log2ns)) < 128)) --log2ns;
+    log2T -= log2ns;
+    const int32_t* row_ids = p->row_ids.p ? p->row_ids.as<int32_t>() : nullptr;
     if (sc->n_split_rows > 0) {
         const int64_t total = sc->n_split_rows * F;
         hipLaunchKernelGGL(k_zero_rows, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
-                           sc->split_dst.as<int32_t>(), sc->n_split_rows, F, out);
+                           sc->cut_rows.as<int32_t>(), sc->n_split_rows, row_ids, F, out);
     }
-    const unsigned blocks = (unsigned)((waves + (kBlock / 64) - 1) / (kBlock / 64));
-    switch (vec) {
-        case 4: launch_vec<4>(log2T, blocks, s, p, sc, in, out, F, tab); break;
-        case 2: launch_vec<2>(log2T, blocks, s, p, sc, in, out, F, tab); break;
-        default: launch_vec<1>(log2T, blocks, s, p, sc, in, out, F, tab); break;
+    if (p->n_empty_rows > 0) {  // all-active graph: vertices without any entry become zero
+        const int64_t total = p->n_empty_rows * F;
+        hipLaunchKernelGGL(k_zero_rows, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
+                           p->empty_rows.as<int32_t>(), p->n_empty_rows, (const int32_t*)nullptr, F, out);
+    }
+    if (sc->n_groups > 0) {
+        AggArgs a;
+        a.cv = reinterpret_cast<const int2v*>(p->cv.p);
+        a.group_row = sc->group_row.as<int32_t>();
+        a.row_ids = row_ids;
+        a.in = in;
+        a.out = out;
+        a.nnz = p->nnz;
+        a.n_groups = sc->n_groups;
+        a.F = F;
+        a.gs = sc->gs;
+        a.log2ns = log2ns;
+        // sc->unroll counts 16-byte gathers in flight per lane: narrower lanes issue more of them
+        const int u = std::min(sc->unroll * (vec == 4 ? 1 : 2), 16);
+        switch (u) {
+            case 4: launch_u<4>(vec, log2T, s, a); break;
+            case 8: launch_u<8>(vec, log2T, s, a); break;
+            default: launch_u<16>(vec, log2T, s, a); break;
+        }
     }
     EPP_HIP_TRY(hipGetLastError());
     return EPP_OK;

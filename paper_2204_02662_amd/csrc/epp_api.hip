@@ -12,7 +12,7 @@ thread_local char g_err[512] = "";
 epp_path::WidthCfg* width_cfg(epp_path* p, int F) {
     for (auto& w : p->widths)
         if (w.F == F) return &w;
-    p->widths.push_back(epp_path::WidthCfg{F, 0, 0, nullptr});
+    p->widths.push_back(epp_path::WidthCfg{F, 0, nullptr});
     return &p->widths.back();
 }
 
@@ -42,7 +42,7 @@ int aggregate(epp_path* p, const float* in, float* out, int F, hipStream_t s) {
     if (in == out) { epp_set_error("grad_in and grad_out must not alias"); return EPP_ERR_INVALID_ARG; }
     epp_path::WidthCfg* w = nullptr;
     EPP_TRY(ensure_schedule(p, F, s, &w));
-    return epp_launch_aggregate(p, w->sched, w->lanes_hint, in, out, F, s);
+    return epp_launch_aggregate(p, w->sched, in, out, F, s);
 }
 
 }  // namespace
@@ -65,7 +65,7 @@ extern "C" int epp_path_info(const epp_path_t* p, epp_path_info_t* info) {
     info->n_src = p->n_src;
     info->max_len = p->max_len;
     for (int c = 0; c < EPP_NCLASS; ++c) info->len_hist[c] = p->len_hist[c];
-    size_t bytes = p->row_ids.bytes + p->rowptr.bytes + p->cv.bytes;
+    size_t bytes = p->row_ids.bytes + p->rowptr.bytes + p->cv.bytes + p->full_rowptr.bytes + p->empty_rows.bytes;
     for (const Schedule* s : p->scheds) bytes += s->bytes();
     info->bytes = (int64_t)bytes;
     for (const auto& w : p->widths) {
@@ -85,16 +85,11 @@ extern "C" int epp_select_group_size(const epp_path_t* p, int F) {
     return epp_default_group_size(p, F);
 }
 
-extern "C" int epp_path_set_group_size(epp_path_t* p, int F, int gs, int lanes_per_row_hint, epp_stream_t stream) {
+extern "C" int epp_path_set_group_size(epp_path_t* p, int F, int gs, epp_stream_t stream) {
     if (!p) { epp_set_error("path is NULL"); return EPP_ERR_INVALID_ARG; }
     if (F < 1) { epp_set_error("F must be >= 1"); return EPP_ERR_INVALID_ARG; }
-    if (lanes_per_row_hint < 0 || lanes_per_row_hint > 64 || (lanes_per_row_hint & (lanes_per_row_hint - 1))) {
-        epp_set_error("lanes_per_row_hint must be 0 or a power of two <= 64");
-        return EPP_ERR_INVALID_ARG;
-    }
     epp_path::WidthCfg* w = width_cfg(p, F);
     w->forced_gs = gs > 0 ? gs : 0;
-    w->lanes_hint = lanes_per_row_hint;
     w->sched = nullptr;
     // drop cached tables that no width refers to any more
     for (size_t i = 0; i < p->scheds.size();) {

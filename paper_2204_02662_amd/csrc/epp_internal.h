@@ -62,37 +62,40 @@ struct DevBuf {
     template <class T> T* as() const { return static_cast<T*>(p); }
 };
 
-// Group table of one path for one group size gs (neighbour grouping, Sec. 2.2): every row
-// is cut into consecutive groups of at most gs entries.  Groups are binned by length class
-// (class c holds lengths in (2^(c-1), 2^c], class 0 lengths 0 and 1) so that a wavefront
-// only ever works on groups of similar length.
+// Group table of one path for one group size gs (neighbour grouping, Sec. 2.2): the path's
+// entry array is cut into groups of gs consecutive entries; group g covers entries
+// [g * gs, min((g + 1) * gs, nnz)).
 struct Schedule {
     int gs = 0;
+    int unroll = 8;            // gathers in flight per lane (kernel template parameter)
+    int log2_slices = 0;       // feature slices spread over the XCDs (request; clipped per width)
     int64_t n_groups = 0;
-    int64_t n_split_rows = 0;
-    int64_t class_count[EPP_NCLASS] = {};  // groups per class
-    int64_t class_begin[EPP_NCLASS] = {};  // first group of the class in the arrays below
-    DevBuf g_start;    // int32[n_groups]  first entry of the group in cv
-    DevBuf g_len;      // int32[n_groups]  entries; bit 31 set: row is split -> atomic write-back
-    DevBuf g_dst;      // int32[n_groups]  destination vertex
-    DevBuf split_dst;  // int32[n_split_rows]  vertices whose rows must be zeroed before atomics
-    size_t bytes() const { return g_start.bytes + g_len.bytes + g_dst.bytes + split_dst.bytes; }
+    int64_t n_split_rows = 0;  // rows cut by a group boundary (written with atomics)
+    DevBuf group_row;          // int32[n_groups] row holding the group's first entry; bit 31: starts inside it
+    DevBuf cut_rows;           // int32[n_split_rows] (path-row indices) zeroed before every launch
+    size_t bytes() const { return group_row.bytes + cut_rows.bytes; }
 };
 
 struct epp_path {
     int64_t n = 0;       // vertices of the input graph
-    int64_t n_rows = 0;  // R
+    int64_t n_rows = 0;  // R: rows of the path in canonical form (all-active graph: n)
     int64_t nnz = 0;
     int64_t n_src = 0;
     int64_t max_len = 0;
     int64_t len_hist[EPP_NCLASS] = {};
-    bool all_rows = false;  // all-active graph: row r is vertex r, row_ids unused
-    DevBuf row_ids;         // int32[R] ascending vertex ids
-    DevBuf rowptr;          // int32[R+1]
-    DevBuf cv;              // int2[nnz]: (column id, weight bits) interleaved
+    bool all_rows = false;       // all-active graph (handle from epp_prepare_full)
+    // Streamed form: only rows with at least one entry, in ascending vertex order.
+    int64_t n_stream_rows = 0;
+    DevBuf row_ids;              // int32[n_stream_rows] vertex of each streamed row; unset: identity
+    DevBuf rowptr;               // int32[n_stream_rows + 1]
+    DevBuf cv;                   // int2[nnz]: (column id | row-end flag in bit 31, weight bits)
+    // all-active graph only
+    DevBuf full_rowptr;          // int32[n + 1] as given (for export)
+    int64_t n_empty_rows = 0;
+    DevBuf empty_rows;           // int32[n_empty_rows] vertices with empty lists
     std::vector<Schedule*> scheds;
     // per-width choices
-    struct WidthCfg { int F; int forced_gs; int lanes_hint; Schedule* sched; };
+    struct WidthCfg { int F; int forced_gs; Schedule* sched; };
     std::vector<WidthCfg> widths;
     int last_F = 0;
     ~epp_path() { for (Schedule* s : scheds) delete s; }
@@ -112,6 +115,6 @@ int epp_path_finish(epp_path* p, hipStream_t s);  // histogram + max length of a
 
 // aggregate.hip
 int epp_build_schedule(epp_path* p, int gs, hipStream_t s, Schedule** out);
-int epp_launch_aggregate(epp_path* p, Schedule* sc, int lanes_hint, const float* in, float* out, int F,
-                         hipStream_t s);
+int epp_launch_aggregate(epp_path* p, Schedule* sc, const float* in, float* out, int F, hipStream_t s);
+int epp_unroll();
 int epp_default_group_size(const epp_path* p, int F);

@@ -240,7 +240,7 @@ __global__ __launch_bounds__(kBlock) void k_deinterleave(const int2* __restrict_
     int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (e < nnz) {
         int2 x = cv[e];
-        if (col) col[e] = x.x;
+        if (col) col[e] = x.x & 0x7FFFFFFF;  // bit 31 is the row-end flag
         if (val) val[e] = __int_as_float(x.y);
     }
 }
@@ -248,6 +248,25 @@ __global__ __launch_bounds__(kBlock) void k_deinterleave(const int2* __restrict_
 __global__ __launch_bounds__(kBlock) void k_iota(int32_t* __restrict__ out, int64_t n) {
     int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (i < n) out[i] = (int32_t)i;
+}
+
+// Flag the last entry of every (non-empty) row in bit 31 of its column id.
+__global__ __launch_bounds__(kBlock) void k_mark_row_ends(const int32_t* __restrict__ rowptr, int64_t n_rows,
+                                                          int2* __restrict__ cv) {
+    int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (r >= n_rows) return;
+    int32_t end = rowptr[r + 1];
+    if (end > rowptr[r]) cv[end - 1].x |= (int)0x80000000u;
+}
+
+// Bitmap of the vertices with a non-empty (invert = 0) or empty (invert = 1) list.
+__global__ __launch_bounds__(kBlock) void k_nonempty_bitmap(const int32_t* __restrict__ rowptr, int64_t n, int invert,
+                                                            unsigned long long* __restrict__ bitmap) {
+    int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    bool flag = false;
+    if (v < n) flag = (rowptr[v + 1] > rowptr[v]) != (invert != 0);
+    unsigned long long bal = __ballot(flag);
+    if (lane_id() == 0 && (v >> 6) < ((n + 63) >> 6)) bitmap[v >> 6] = bal;
 }
 
 inline unsigned grid_for(int64_t n, int per_block) { return (unsigned)((n + per_block - 1) / per_block); }
@@ -318,7 +337,9 @@ int epp_path_finish(epp_path* p, hipStream_t s) {
     EPP_TRY(stats.alloc((EPP_NCLASS + 1) * sizeof(unsigned long long)));
     EPP_HIP_TRY(hipMemsetAsync(stats.p, 0, stats.bytes, s));
     if (p->n_rows > 0) {
-        hipLaunchKernelGGL(k_len_hist, dim3(grid_for(p->n_rows, kBlock)), dim3(kBlock), 0, s, p->rowptr.as<int32_t>(),
+        // canonical rows: the all-active graph counts its empty rows too
+        const int32_t* ptr = p->all_rows ? p->full_rowptr.as<int32_t>() : p->rowptr.as<int32_t>();
+        hipLaunchKernelGGL(k_len_hist, dim3(grid_for(p->n_rows, kBlock)), dim3(kBlock), 0, s, ptr,
                            p->n_rows, stats.as<unsigned long long>(),
                            reinterpret_cast<int*>(stats.as<unsigned long long>() + EPP_NCLASS));
         EPP_HIP_TRY(hipGetLastError());
@@ -330,6 +351,12 @@ int epp_path_finish(epp_path* p, hipStream_t s) {
     int mx;
     std::memcpy(&mx, &host[EPP_NCLASS], sizeof(int));
     p->max_len = mx;
+    if (p->n_stream_rows > 0) {
+        hipLaunchKernelGGL(k_mark_row_ends, dim3(grid_for(p->n_stream_rows, kBlock)), dim3(kBlock), 0, s,
+                           p->rowptr.as<int32_t>(), p->n_stream_rows, p->cv.as<int2>());
+        EPP_HIP_TRY(hipGetLastError());
+        EPP_HIP_TRY(hipStreamSynchronize(s));
+    }
     return EPP_OK;
 }
 
@@ -423,6 +450,7 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
         EPP_TRY(compact_bitmap(P->bitmaps[k + 1], n, newptr.as<int>(), (int)kept, &p->row_ids, &p->rowptr,
                                &P->set_size[k + 1], tile_cnt, tile_base, dev_total, hs, s));
         p->n_rows = P->set_size[k + 1];
+        p->n_stream_rows = p->n_rows;  // every row of a path has at least one entry
         EPP_TRY(epp_path_finish(p, s));
     }
     EPP_HIP_TRY(hipStreamSynchronize(s));
@@ -443,13 +471,44 @@ extern "C" int epp_prepare_full(const epp_csr_t* g, epp_stream_t stream, epp_pat
     p->nnz = g->nnz;
     p->n_src = g->n;
     p->all_rows = true;
-    EPP_TRY(p->rowptr.alloc((size_t)(g->n + 1) * 4));
+    EPP_TRY(p->full_rowptr.alloc((size_t)(g->n + 1) * 4));
     EPP_TRY(p->cv.alloc((size_t)g->nnz * sizeof(int2)));
-    EPP_HIP_TRY(hipMemcpyAsync(p->rowptr.p, g->rowptr, (size_t)(g->n + 1) * 4, hipMemcpyDeviceToDevice, s));
+    EPP_HIP_TRY(hipMemcpyAsync(p->full_rowptr.p, g->rowptr, (size_t)(g->n + 1) * 4, hipMemcpyDeviceToDevice, s));
     if (g->nnz > 0) {
         hipLaunchKernelGGL(k_interleave, dim3(grid_for(g->nnz, kBlock)), dim3(kBlock), 0, s, g->col, g->val, g->nnz,
                            p->cv.as<int2>());
         EPP_HIP_TRY(hipGetLastError());
+    }
+    {   // streamed form: the vertices with non-empty lists, ascending, with a compact row pointer
+        HostScalars hs;
+        EPP_TRY(hs.init());
+        DevBuf bitmap, tile_cnt, tile_base, dev_total;
+        const int64_t n_words = (g->n + 63) / 64;
+        const size_t tiles = std::max<size_t>(grid_for(n_words, kWordsPerTile), 1);
+        EPP_TRY(bitmap.alloc((size_t)n_words * 8));
+        EPP_TRY(tile_cnt.alloc(tiles * 4));
+        EPP_TRY(tile_base.alloc(tiles * 4));
+        EPP_TRY(dev_total.alloc(sizeof(long long)));
+        if (g->n > 0) {
+            hipLaunchKernelGGL(k_nonempty_bitmap, dim3(grid_for(g->n, kBlock)), dim3(kBlock), 0, s, g->rowptr, g->n, 0,
+                               bitmap.as<unsigned long long>());
+            EPP_HIP_TRY(hipGetLastError());
+        }
+        EPP_TRY(compact_bitmap(bitmap, g->n, g->rowptr, (int)g->nnz, &p->row_ids, &p->rowptr, &p->n_stream_rows,
+                               tile_cnt, tile_base, dev_total, hs, s));
+        p->n_empty_rows = g->n - p->n_stream_rows;
+        if (p->n_empty_rows == 0) {
+            EPP_HIP_TRY(hipStreamSynchronize(s));
+            p->row_ids.release();  // identity
+        } else {
+            hipLaunchKernelGGL(k_nonempty_bitmap, dim3(grid_for(g->n, kBlock)), dim3(kBlock), 0, s, g->rowptr, g->n, 1,
+                               bitmap.as<unsigned long long>());
+            EPP_HIP_TRY(hipGetLastError());
+            int64_t cnt = 0;
+            EPP_TRY(compact_bitmap(bitmap, g->n, nullptr, 0, &p->empty_rows, nullptr, &cnt, tile_cnt, tile_base,
+                                   dev_total, hs, s));
+            EPP_HIP_TRY(hipStreamSynchronize(s));
+        }
     }
     EPP_TRY(epp_path_finish(p, s));
     guard.p = nullptr;
@@ -478,7 +537,10 @@ extern "C" int epp_path_export(const epp_path_t* p, int32_t* row_ids, int32_t* r
             EPP_HIP_TRY(hipMemcpyAsync(row_ids, p->row_ids.p, (size_t)p->n_rows * 4, hipMemcpyDeviceToDevice, s));
         }
     }
-    if (rowptr) EPP_HIP_TRY(hipMemcpyAsync(rowptr, p->rowptr.p, (size_t)(p->n_rows + 1) * 4, hipMemcpyDeviceToDevice, s));
+    if (rowptr) {
+        const void* ptr = p->all_rows ? p->full_rowptr.p : p->rowptr.p;
+        EPP_HIP_TRY(hipMemcpyAsync(rowptr, ptr, (size_t)(p->n_rows + 1) * 4, hipMemcpyDeviceToDevice, s));
+    }
     if ((col || val) && p->nnz > 0) {
         hipLaunchKernelGGL(k_deinterleave, dim3(grid_for(p->nnz, kBlock)), dim3(kBlock), 0, s, p->cv.as<int2>(), p->nnz,
                            col, val);
