@@ -73,20 +73,19 @@ def cpu_baseline(cfg, budget_s: float):
         if R == 0:
             strides.append(1)
             continue
-        # calibrate on a thin sample, then size the real sample to this layer's share of the budget
-        s0 = max(1, R // 2000)
-        t = time.perf_counter()
-        oracle.path_aggregate(g.n, po, X, first=0, stride=s0)
-        t_cal = max(time.perf_counter() - t, 1e-4)
+        # size the sample to this layer's share of the budget: start thin, then widen from
+        # the measured rate until the run is long enough (cold caches make thin samples slow)
         lens = np.diff(po.rowptr)
-        frac_cal = lens[0::s0].sum() / max(po.col.size, 1)
-        full_est = t_cal / max(frac_cal, 1e-9)
         share = budget_s * work[l] / total_work
-        stride = max(1, int(np.ceil(full_est / max(share, 1e-3))))
-        t = time.perf_counter()
-        oracle.path_aggregate(g.n, po, X, first=0, stride=stride)
-        dt = time.perf_counter() - t
-        frac = lens[0::stride].sum() / max(po.col.size, 1)
+        stride = max(1, R // 2000)
+        while True:
+            t = time.perf_counter()
+            oracle.path_aggregate(g.n, po, X, first=0, stride=stride)
+            dt = max(time.perf_counter() - t, 1e-4)
+            frac = lens[0::stride].sum() / max(po.col.size, 1)
+            if stride == 1 or dt >= 0.5 * share:
+                break
+            stride = max(1, min(stride - 1, int(stride * dt / share)))
         est_ms += dt / max(frac, 1e-12) * 1e3
         sampled_s += dt
         strides.append(stride)
