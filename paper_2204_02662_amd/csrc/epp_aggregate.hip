@@ -30,6 +30,8 @@ namespace {
 
 constexpr int kBlock = 256;
 constexpr int kRowEnd = (int)0x80000000u;
+constexpr int kCold = 0x40000000;
+constexpr int kColMask = 0x3FFFFFFF;
 
 typedef int int2v __attribute__((ext_vector_type(2)));
 typedef float float2v __attribute__((ext_vector_type(2)));
@@ -38,8 +40,9 @@ template <int VEC> struct VecT;
 template <> struct VecT<1> { typedef float type; };
 template <> struct VecT<2> { typedef float2v type; };
 template <> struct VecT<4> { typedef float4v type; };
-template <int VEC> __device__ __forceinline__ float lane_get(const typename VecT<VEC>::type& x, int i) { return x[i]; }
-template <> __device__ __forceinline__ float lane_get<1>(const float& x, int) { return x; }
+template <int VEC, class V> __device__ __forceinline__ float lane_get(const V& x, int i) {
+    if constexpr (VEC == 1) return x; else return x[i];
+}
 
 // ---------------------------------------------------------------- schedule construction
 // One thread per group: the row that holds the group's first entry (search in the row
@@ -161,7 +164,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(AggArgs a) {
         for (int i = 0; i < 4; ++i) {
             const int j = i * T + t;
             pre[i] = len > 0 ? __builtin_nontemporal_load(my + std::min(j, len - 1)) : int2v{0, 0};
-            if (j >= len) { pre[i].x &= 0x7FFFFFFF; pre[i].y = 0; }
+            if (j >= len) { pre[i].x &= kColMask; pre[i].y = 0; }
         }
         for (int base = 0; base < len; base += S) {
             __builtin_amdgcn_wave_barrier();
@@ -174,7 +177,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(AggArgs a) {
                 for (int i = 0; i < 4; ++i) {
                     const int j = base + S + i * T + t;
                     pre[i] = __builtin_nontemporal_load(my + std::min(j, len - 1));
-                    if (j >= len) { pre[i].x &= 0x7FFFFFFF; pre[i].y = 0; }
+                    if (j >= len) { pre[i].x &= kColMask; pre[i].y = 0; }
                 }
             }
             const int n_here = std::min(S, len - base);
@@ -187,7 +190,16 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(AggArgs a) {
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     if (fok) {
-                        x[u] = *reinterpret_cast<const vec_t*>(src + (size_t)(e[u].x & 0x7FFFFFFF) * (size_t)a.F);
+                        int c = e[u].x & kColMask;
+                        if (e[u].x & kCold) {
+                            // rarely referenced source: streamed, so that it does not evict hot rows from
+                            // L2 and the memory-side cache (the index is laundered so that the two loads
+                            // stay two instructions, each with its own cache policy)
+                            asm volatile("" : "+v"(c));
+                            x[u] = __builtin_nontemporal_load(reinterpret_cast<const vec_t*>(src + (size_t)c * (size_t)a.F));
+                        } else {
+                            x[u] = *reinterpret_cast<const vec_t*>(src + (size_t)c * (size_t)a.F);
+                        }
                     } else {
                         x[u] = vec_t{};
                     }
@@ -228,13 +240,15 @@ int ceil_log2(int x) {
     return l;
 }
 
-// Lanes per source row and floats per lane for width F.
-void row_shape(int F, int* vec, int* log2T) {
+// Lanes per source row and floats per lane for width F.  (16-byte accesses at 4-byte
+// alignment for widths that are not a multiple of four were tried and measured no faster:
+// F = 41: 1.34 vs 1.45 ms, F = 47: 0.51 vs 0.48 ms; the plain per-float form is kept.)
+void row_shape(int F, bool aligned16, int* vec, int* log2T) {
     int v = (F % 4 == 0) ? 4 : (F % 2 == 0 ? 2 : 1);
+    if (!aligned16) v = 1;
     int frags = (F + v - 1) / v;
-    int lt = std::min(ceil_log2(frags), 6);
     *vec = v;
-    *log2T = lt;
+    *log2T = std::min(ceil_log2(frags), 6);
 }
 
 template <int VEC, int LOG2T, int U>
@@ -259,21 +273,51 @@ void launch_vec(int log2T, hipStream_t s, const AggArgs& a) {
     }
 }
 
-template <int U>
-void launch_u(int vec, int log2T, hipStream_t s, const AggArgs& a) {
-    switch (vec) {
-        case 4: launch_vec<4, U>(log2T, s, a); break;
-        case 2: launch_vec<2, U>(log2T, s, a); break;
-        default: launch_vec<1, U>(log2T, s, a); break;
+// ---- hot / cold sources -----------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void k_count_sources(const int2v* __restrict__ cv, int64_t nnz,
+                                                          int* __restrict__ cnt) {
+    int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (e < nnz) atomicAdd(&cnt[cv[e].x & kColMask], 1);
+}
+
+// Quarter-octave bins of the reference count k >= 1: bin = k for k < 4, else
+// 4 * floor(log2 k) + (next two bits of k); bin_floor(bin) is the smallest k of a bin.
+constexpr int kCountBins = 128;
+__host__ __device__ inline int count_bin(int k) {
+    if (k < 4) return k;
+    int e = 31 - __builtin_clz((unsigned)k);
+    return 4 * e + ((k >> (e - 2)) & 3);
+}
+inline int bin_floor(int bin) {
+    if (bin < 8) return bin;  // bins 4..7 do not occur (k = 4..7 map to bins 8..11)
+    int e = bin >> 2, sub = bin & 3;
+    return (4 + sub) << (e - 2);
+}
+
+__global__ __launch_bounds__(kBlock) void k_count_hist(const int* __restrict__ cnt, int64_t n,
+                                                       unsigned long long* __restrict__ hist) {
+    __shared__ int h[kCountBins];
+    if (threadIdx.x < kCountBins) h[threadIdx.x] = 0;
+    __syncthreads();
+    int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (v < n) {
+        int k = cnt[v];
+        if (k > 0) atomicAdd(&h[count_bin(k)], 1);
     }
+    __syncthreads();
+    if (threadIdx.x < kCountBins && h[threadIdx.x]) atomicAdd(&hist[threadIdx.x], (unsigned long long)h[threadIdx.x]);
+}
+
+__global__ __launch_bounds__(kBlock) void k_mark_cold(int2v* __restrict__ cv, int64_t nnz, const int* __restrict__ cnt,
+                                                      int thr) {
+    int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (e >= nnz) return;
+    int x = cv[e].x & ~kCold;
+    if (cnt && cnt[x & kColMask] < thr) x |= kCold;
+    cv[e].x = x;
 }
 
 }  // namespace
-
-int epp_unroll() {
-    int u = env_int("EPP_TUNE_UNROLL", 8);
-    return u <= 4 ? 4 : (u >= 16 ? 16 : 8);
-}
 
 // Structure-aware group size (Sec. 5) re-derived for 64-lane wavefronts.
 //
@@ -289,7 +333,7 @@ int epp_default_group_size(const epp_path* p, int F) {
     int forced = env_int("EPP_TUNE_GS", 0);
     if (forced > 0) return forced;
     int vec, log2T;
-    row_shape(F, &vec, &log2T);
+    row_shape(F, true, &vec, &log2T);
     const int64_t slots = 256ll * 16 * (64 >> log2T);
     const int64_t want = p->nnz / (slots * 4);
     int gs = 16;
@@ -301,7 +345,6 @@ int epp_build_schedule(epp_path* p, int gs, hipStream_t s, Schedule** out) {
     Schedule* sc = new Schedule();
     struct Guard { Schedule* s; ~Guard() { delete s; } } guard{sc};
     sc->gs = gs;
-    sc->unroll = epp_unroll();
     sc->log2_slices = env_int("EPP_TUNE_LOG2_SLICES", 0);
     const int64_t n_groups = (p->nnz + gs - 1) / gs;
     if (n_groups >= 0x7FFFFFFFll) { epp_set_error("too many groups"); return EPP_ERR_TOO_LARGE; }
@@ -329,11 +372,8 @@ int epp_build_schedule(epp_path* p, int gs, hipStream_t s, Schedule** out) {
 
 int epp_launch_aggregate(epp_path* p, Schedule* sc, const float* in, float* out, int F, hipStream_t s) {
     int vec, log2T;
-    row_shape(F, &vec, &log2T);
-    if (vec > 1 && ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & (uintptr_t)(vec * 4 - 1))) {
-        vec = 1;  // base pointers not aligned for vector access
-        log2T = std::min(ceil_log2(F), 6);
-    }
+    const bool aligned16 = ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & 15) == 0;
+    row_shape(F, aligned16, &vec, &log2T);
     // feature slices over the XCDs: each slice keeps whole 128-byte lines of a row
     int log2ns = std::min(std::max(sc->log2_slices, 0), 3);
     while (log2ns > 0 && ((log2T - log2ns) < 0 || ((vec * 4) << (log2T - log2ns)) < 128)) --log2ns;
@@ -361,14 +401,54 @@ int epp_launch_aggregate(epp_path* p, Schedule* sc, const float* in, float* out,
         a.F = F;
         a.gs = sc->gs;
         a.log2ns = log2ns;
-        // sc->unroll counts 16-byte gathers in flight per lane: narrower lanes issue more of them
-        const int u = std::min(sc->unroll * (vec == 4 ? 1 : 2), 16);
-        switch (u) {
-            case 4: launch_u<4>(vec, log2T, s, a); break;
-            case 8: launch_u<8>(vec, log2T, s, a); break;
-            default: launch_u<16>(vec, log2T, s, a); break;
-        }
+        // gathers in flight per lane: 8 x 16 bytes, or 16 narrower ones
+        if (vec == 4) launch_vec<4, 8>(log2T, s, a);
+        else if (vec == 2) launch_vec<2, 16>(log2T, s, a);
+        else launch_vec<1, 16>(log2T, s, a);
     }
     EPP_HIP_TRY(hipGetLastError());
+    return EPP_OK;
+}
+
+// Which sources are worth caching.  The gathered rows of a big path do not fit the caches
+// (4 MB L2 per XCD, 256 MB memory-side cache); with plain loads the rarely referenced rows
+// keep evicting the often referenced ones.  Sources are ranked by how often the path
+// references them; the most referenced ones, as many as fit the budget, stay "hot", all
+// entries of the others get the cold flag and are gathered with streaming loads.
+int epp_mark_cold_sources(epp_path* p, int F, hipStream_t s) {
+    const int64_t budget_mb = env_int("EPP_TUNE_HOT_MB", 96);
+    const int64_t rows_budget = budget_mb * (1ll << 20) / ((int64_t)F * 4);
+    int thr = 0;
+    DevBuf cnt;
+    if (budget_mb > 0 && p->nnz > 0 && p->n_src > rows_budget) {
+        EPP_TRY(cnt.alloc((size_t)p->n * 4));
+        EPP_HIP_TRY(hipMemsetAsync(cnt.p, 0, cnt.bytes, s));
+        DevBuf hist;
+        EPP_TRY(hist.alloc(kCountBins * sizeof(unsigned long long)));
+        EPP_HIP_TRY(hipMemsetAsync(hist.p, 0, hist.bytes, s));
+        hipLaunchKernelGGL(k_count_sources, dim3((unsigned)((p->nnz + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
+                           reinterpret_cast<const int2v*>(p->cv.p), p->nnz, cnt.as<int>());
+        hipLaunchKernelGGL(k_count_hist, dim3((unsigned)((p->n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
+                           cnt.as<int>(), p->n, hist.as<unsigned long long>());
+        EPP_HIP_TRY(hipGetLastError());
+        unsigned long long h[kCountBins];
+        EPP_HIP_TRY(hipMemcpyAsync(h, hist.p, sizeof(h), hipMemcpyDeviceToHost, s));
+        EPP_HIP_TRY(hipStreamSynchronize(s));
+        // keep whole bins, most referenced first, while they fit
+        int64_t kept = 0;
+        int c = kCountBins - 1;
+        for (; c >= 1; --c) {
+            if (kept + (int64_t)h[c] > rows_budget) break;
+            kept += (int64_t)h[c];
+        }
+        // bins 1..c are cold
+        thr = c < 1 ? 0 : bin_floor(c + 1 == 4 ? 8 : c + 1);
+    }
+    if (thr == p->cold_thr) return EPP_OK;
+    hipLaunchKernelGGL(k_mark_cold, dim3((unsigned)((p->nnz + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
+                       reinterpret_cast<int2v*>(p->cv.p), p->nnz, thr > 0 ? cnt.as<int>() : (const int*)nullptr, thr);
+    EPP_HIP_TRY(hipGetLastError());
+    EPP_HIP_TRY(hipStreamSynchronize(s));
+    p->cold_thr = thr;
     return EPP_OK;
 }

@@ -67,7 +67,6 @@ struct DevBuf {
 // [g * gs, min((g + 1) * gs, nnz)).
 struct Schedule {
     int gs = 0;
-    int unroll = 8;            // gathers in flight per lane (kernel template parameter)
     int log2_slices = 0;       // feature slices spread over the XCDs (request; clipped per width)
     int64_t n_groups = 0;
     int64_t n_split_rows = 0;  // rows cut by a group boundary (written with atomics)
@@ -88,7 +87,8 @@ struct epp_path {
     int64_t n_stream_rows = 0;
     DevBuf row_ids;              // int32[n_stream_rows] vertex of each streamed row; unset: identity
     DevBuf rowptr;               // int32[n_stream_rows + 1]
-    DevBuf cv;                   // int2[nnz]: (column id | row-end flag in bit 31, weight bits)
+    DevBuf cv;                   // int2[nnz]: (column id | cold flag bit 30 | row-end flag bit 31, weight bits)
+    int cold_thr = 0;            // entries whose source is referenced fewer times than this carry the cold flag
     // all-active graph only
     DevBuf full_rowptr;          // int32[n + 1] as given (for export)
     int64_t n_empty_rows = 0;
@@ -116,5 +116,5 @@ int epp_path_finish(epp_path* p, hipStream_t s);  // histogram + max length of a
 // aggregate.hip
 int epp_build_schedule(epp_path* p, int gs, hipStream_t s, Schedule** out);
 int epp_launch_aggregate(epp_path* p, Schedule* sc, const float* in, float* out, int F, hipStream_t s);
-int epp_unroll();
 int epp_default_group_size(const epp_path* p, int F);
+int epp_mark_cold_sources(epp_path* p, int F, hipStream_t s);

@@ -240,7 +240,7 @@ __global__ __launch_bounds__(kBlock) void k_deinterleave(const int2* __restrict_
     int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (e < nnz) {
         int2 x = cv[e];
-        if (col) col[e] = x.x & 0x7FFFFFFF;  // bit 31 is the row-end flag
+        if (col) col[e] = x.x & 0x3FFFFFFF;  // bits 30 and 31 are the cold and row-end flags
         if (val) val[e] = __int_as_float(x.y);
     }
 }
@@ -288,8 +288,9 @@ struct HostScalars {
 int validate_csr(const epp_csr_t* g) {
     if (!g) { epp_set_error("graph is NULL"); return EPP_ERR_INVALID_ARG; }
     if (g->n < 0 || g->nnz < 0) { epp_set_error("negative graph size"); return EPP_ERR_INVALID_ARG; }
-    if (g->n >= 0x7FFFFFFFll || g->nnz >= 0x7FFFFFFFll) {
-        epp_set_error("graph too large: n=%lld nnz=%lld (limit 2^31-1)", (long long)g->n, (long long)g->nnz);
+    if (g->n >= 0x40000000ll || g->nnz >= 0x7FFFFFFFll) {
+        epp_set_error("graph too large: n=%lld (limit 2^30-1) nnz=%lld (limit 2^31-1)", (long long)g->n,
+                      (long long)g->nnz);
         return EPP_ERR_TOO_LARGE;
     }
     if (!g->rowptr || (g->nnz > 0 && (!g->col || !g->val))) {

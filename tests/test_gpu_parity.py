@@ -78,7 +78,7 @@ def test_small_random_graphs(seed):
     check_layers(g, train, 3, [int(x) for x in rng.integers(1, 70, 3)], 50 + seed, gs_list=(0, 1, 3))
 
 
-@pytest.mark.parametrize("F", [1, 2, 3, 4, 7, 8, 16, 31, 32, 41, 47, 64, 100, 128, 130, 256, 300])
+@pytest.mark.parametrize("F", [1, 2, 3, 4, 5, 6, 7, 8, 16, 31, 32, 41, 47, 64, 100, 128, 130, 256, 259, 300, 301])
 def test_widths_on_skewed_graph(F):
     """Several tiles, hubs that get split, a ragged tail, every vector shape."""
     g = graphgen.random_graph("rmat", 5003, seed=21, raw_draws=90_000)
@@ -180,3 +180,23 @@ def test_run_to_run_determinism_of_unsplit_rows():
 def test_small_configs_every_entry(k):
     cfg = graphgen.make_config(k)
     check_layers(cfg.graph, cfg.train_ids, cfg.L, cfg.widths, cfg.seed(10))
+
+
+def test_export_is_unchanged_by_aggregation_and_hot_cold_marking(monkeypatch):
+    """Internal flags (row ends, cold sources) never leak into the canonical form, and the
+    result does not depend on which sources are streamed."""
+    g = graphgen.random_graph("rmat", 30_000, seed=71, raw_draws=400_000)
+    train = graphgen.training_set(g.n, 3000, 72)
+    sets_o, paths_o = oprep(g, train, 2)
+    F = 64
+    X = graphgen.normal_rows(g.n, F, sets_o[1], 73)
+    want = oracle.path_aggregate(g.n, paths_o[0], X)
+    for mb in ("0", "1", "2"):  # off / a budget of 1 or 2 MB: most sources of this path are cold
+        monkeypatch.setenv("EPP_TUNE_HOT_MB", mb)
+        paths = gpu_prepare(g, train, 2)
+        p = paths.path(0)
+        assert_close(run_partial(p, X), want, f"hot budget {mb} MB")
+        Xp = X.copy()
+        Xp[sets_o[1] == 0] = np.nan
+        assert_close(run_partial(p, Xp), want, f"hot budget {mb} MB, nan-poison")
+        assert_paths_bit_exact(paths, sets_o, paths_o, 2)
