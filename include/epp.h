@@ -4,7 +4,8 @@
  * stated otherwise; "host" pointers are ordinary CPU memory.  All calls are made with the
  * target GPU current.  Functions returning int give 0 on success or a negative EPP_ERR_*
  * code; epp_last_error() then holds a human-readable message for the calling thread.  No
- * function aborts or throws across this boundary.
+ * function aborts or throws across this boundary.  A handle (epp_paths_t / epp_path_t) must
+ * not be used by two calls at the same time (calls on one stream, one after the other, are fine).
  *
  * Notation (paper, Table 1 / Sec. 3 / Sec. 4): V_t training set; N^k the k-neighbour set
  * of V_t (vertices reached from V_t by exactly k edges, N^0 = V_t); L layers; SG_l the
@@ -24,7 +25,7 @@ extern "C" {
 #define EPP_OK 0
 #define EPP_ERR_INVALID_ARG (-1)     /* NULL pointer, L < 1, F < 1, negative size ...       */
 #define EPP_ERR_OUT_OF_RANGE_ID (-2) /* a training id outside [0, n)                        */
-#define EPP_ERR_TOO_LARGE (-3)       /* n or nnz >= 2^31                                    */
+#define EPP_ERR_TOO_LARGE (-3)       /* n >= 2^30 or nnz >= 2^31                            */
 #define EPP_ERR_ALLOC (-4)           /* device or host allocation failed                    */
 #define EPP_ERR_HIP (-5)             /* a HIP runtime call failed (message has the detail)  */
 
@@ -36,7 +37,7 @@ typedef void* epp_stream_t; /* a hipStream_t; NULL = the default stream */
  * the library only relies on the order being the caller's canonical one and preserves it).
  * Self-loops are not added: whatever is stored is the operator. */
 typedef struct {
-    int64_t n;             /* number of vertices, < 2^31                        */
+    int64_t n;             /* number of vertices, < 2^30                        */
     int64_t nnz;           /* number of stored entries, < 2^31                  */
     const int32_t* rowptr; /* device, n + 1 entries, rowptr[0] = 0              */
     const int32_t* col;    /* device, nnz entries, each in [0, n)               */
