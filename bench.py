@@ -219,7 +219,9 @@ def main():
         "roofline": roofline,
         "partially_active": {"ms_per_epoch": ms_partial, "sum_layer_ms": sum(layer_ms.values()), "layers": layers},
         "prepare_ms": prepare_ms,
-        "path_bytes_over_csr_bytes": sum(i.bytes for i in infos) / (8.0 * g.nnz + 4.0 * (g.n + 1)),
+        # layers past the fixed point of the active sets share one path object: count it once
+        "path_bytes_over_csr_bytes": sum({path_objs[l]._h: infos[l].bytes for l in range(L)}.values())
+        / (8.0 * g.nnz + 4.0 * (g.n + 1)),
     }
 
     if full is not None:

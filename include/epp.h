@@ -101,6 +101,14 @@ int epp_active_set_export(const epp_paths_t* p, int k, int32_t* ids, int64_t* co
  * row-length histogram.  Pure function of (path, F); returns gs >= 1 or a negative error. */
 int epp_select_group_size(const epp_path_t* p, int F);
 
+/* The paper's linear-regression group size (Sec. 5, the regression equation and its four
+ * coefficients), provided for comparison only: gs = b0 + b1*#vertices + b2*#edges + b3*avgdeg
+ * rounded to the nearest positive integer.  Applied to a (sub-)graph with `vertices` vertices
+ * and `undirected_edges` edges, avgdeg = undirected_edges / vertices as in Table 3.  The
+ * coefficients were fitted on the paper's GPUs and graphs; far outside that domain the value
+ * clamps to 1.  Pure host function. */
+int epp_paper_linreg_group_size(int64_t vertices, int64_t undirected_edges);
+
 /* Force the group size used for width F (sweeps, ablations); gs <= 0 restores the selector.
  * Rebuilds the group table: group g holds entries [g*gs, (g+1)*gs) of the edge array, so a
  * row longer than gs is always cut and short rows share a group.  Synchronises. */

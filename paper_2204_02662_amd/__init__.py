@@ -26,7 +26,7 @@ EXPORTED = [
     "epp_prepare", "epp_prepare_full", "epp_num_layers", "epp_get_path", "epp_path_info",
     "epp_path_export", "epp_active_set_export", "epp_select_group_size", "epp_path_set_group_size",
     "epp_backward_aggregate", "epp_full_aggregate", "epp_destroy_paths", "epp_destroy_path",
-    "epp_last_error",
+    "epp_last_error", "epp_paper_linreg_group_size",
 ]
 
 
@@ -70,6 +70,7 @@ def load_library() -> ctypes.CDLL:
     lib.epp_active_set_export.argtypes = [P, I, P, ctypes.POINTER(I64), P]
     lib.epp_select_group_size.argtypes = [P, I]
     lib.epp_path_set_group_size.argtypes = [P, I, I, P]
+    lib.epp_paper_linreg_group_size.argtypes = [I64, I64]
     lib.epp_backward_aggregate.argtypes = [P, P, P, I, P]
     lib.epp_full_aggregate.argtypes = [P, P, P, I, P]
     lib.epp_destroy_paths.argtypes = [P]
@@ -205,6 +206,11 @@ def epp_prepare_full(n: int, rowptr: torch.Tensor, col: torch.Tensor, val: torch
     out = ctypes.c_void_p()
     _check(lib.epp_prepare_full(ctypes.byref(csr), _stream(), ctypes.byref(out)))
     return Path_(out.value, owned=True)
+
+
+def epp_paper_linreg_group_size(vertices: int, undirected_edges: int) -> int:
+    """Sec. 5 linear-regression group size (comparison only)."""
+    return _check(load_library().epp_paper_linreg_group_size(vertices, undirected_edges))
 
 
 def _grads(path: Path_, grad_in: torch.Tensor, grad_out: torch.Tensor) -> int:

@@ -86,6 +86,17 @@ extern "C" int epp_select_group_size(const epp_path_t* p, int F) {
     return epp_default_group_size(p, F);
 }
 
+extern "C" int epp_paper_linreg_group_size(int64_t vertices, int64_t undirected_edges) {
+    if (vertices < 1 || undirected_edges < 0) { epp_set_error("bad graph size"); return EPP_ERR_INVALID_ARG; }
+    // Sec. 5: least-squares coefficients of the regression equation
+    const double b0 = 0.65538, b1 = 1.67431e-5, b2 = -2.24342e-6, b3 = 0.63641;
+    const double v = (double)vertices, e = (double)undirected_edges;
+    const double x = b0 + b1 * v + b2 * e + b3 * (e / v);
+    if (!(x >= 1.0)) return 1;
+    if (x > 1e9) return 1000000000;
+    return (int)(x + 0.5);
+}
+
 extern "C" int epp_path_set_group_size(epp_path_t* p, int F, int gs, epp_stream_t stream) {
     if (!p) { epp_set_error("path is NULL"); return EPP_ERR_INVALID_ARG; }
     if (F < 1) { epp_set_error("F must be >= 1"); return EPP_ERR_INVALID_ARG; }

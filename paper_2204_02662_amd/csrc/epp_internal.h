@@ -106,8 +106,14 @@ struct epp_paths {
     int64_t n = 0;
     std::vector<DevBuf> bitmaps;    // L+1 bitmaps of N^k, uint64 words
     std::vector<int64_t> set_size;  // |N^k|
-    std::vector<epp_path*> path;    // index l
-    ~epp_paths() { for (epp_path* p : path) delete p; }
+    std::vector<epp_path*> path;    // index l; once the sets stop growing, deeper layers share one object
+    ~epp_paths() {
+        for (size_t i = 0; i < path.size(); ++i) {
+            bool seen = false;
+            for (size_t j = 0; j < i; ++j) seen |= (path[j] == path[i]);
+            if (!seen) delete path[i];
+        }
+    }
 };
 
 // prepare.hip

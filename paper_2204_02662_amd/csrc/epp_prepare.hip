@@ -269,6 +269,14 @@ __global__ __launch_bounds__(kBlock) void k_nonempty_bitmap(const int32_t* __res
     if (lane_id() == 0 && (v >> 6) < ((n + 63) >> 6)) bitmap[v >> 6] = bal;
 }
 
+// flag |= 1 if the two bitmaps differ anywhere.
+__global__ __launch_bounds__(kBlock) void k_bitmap_differs(const unsigned long long* __restrict__ a,
+                                                           const unsigned long long* __restrict__ b, int64_t n_words,
+                                                           int* __restrict__ flag) {
+    int64_t w = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (w < n_words && a[w] != b[w]) atomicOr(flag, 1);
+}
+
 inline unsigned grid_for(int64_t n, int per_block) { return (unsigned)((n + per_block - 1) / per_block); }
 
 // Pinned host staging for the few scalars read back per level.
@@ -453,6 +461,29 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
         p->n_rows = P->set_size[k + 1];
         p->n_stream_rows = p->n_rows;  // every row of a path has at least one entry
         EPP_TRY(epp_path_finish(p, s));
+        // Fixed point: N^{k+1} == N^k means every further set is the same set, so every deeper
+        // layer (rows and sources both equal to it) has exactly this path; share it.
+        if (k + 1 < L && P->set_size[k + 1] == P->set_size[k]) {
+            int differs = 0;
+            EPP_HIP_TRY(hipMemsetAsync(err.p, 0, sizeof(int), s));
+            if (n_words > 0) {
+                hipLaunchKernelGGL(k_bitmap_differs, dim3(grid_for(n_words, kBlock)), dim3(kBlock), 0, s,
+                                   P->bitmaps[k].as<unsigned long long>(), P->bitmaps[k + 1].as<unsigned long long>(),
+                                   n_words, err.as<int>());
+                EPP_HIP_TRY(hipGetLastError());
+            }
+            EPP_HIP_TRY(hipMemcpyAsync(&differs, err.p, sizeof(int), hipMemcpyDeviceToHost, s));
+            EPP_HIP_TRY(hipStreamSynchronize(s));
+            if (!differs) {
+                for (int j = k + 1; j < L; ++j) {
+                    EPP_HIP_TRY(hipMemcpyAsync(P->bitmaps[j + 1].p, P->bitmaps[k + 1].p, P->bitmaps[k + 1].bytes,
+                                               hipMemcpyDeviceToDevice, s));
+                    P->set_size[j + 1] = P->set_size[k + 1];
+                    P->path[L - 1 - j] = p;
+                }
+                break;
+            }
+        }
     }
     EPP_HIP_TRY(hipStreamSynchronize(s));
     guard.p = nullptr;

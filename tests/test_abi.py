@@ -38,3 +38,19 @@ def test_host_side_argument_checks_need_no_gpu():
     out = ctypes.c_void_p()
     assert lib.epp_prepare(None, None, 0, 1, None, ctypes.byref(out)) == epp.EPP_ERR_INVALID_ARG
     assert lib.epp_select_group_size(None, 16) == epp.EPP_ERR_INVALID_ARG
+
+
+def test_paper_linear_regression_group_size():
+    """Sec. 5 regression evaluated on the rows of Table 3 (whole graphs, as printed).  Only the
+    coefficients and the table are printed in the paper, not the resulting group sizes, so this
+    checks plain arithmetic (parity unpinned beyond that)."""
+    import paper_2204_02662_amd as epp
+
+    table3 = [(2708, 5278), (3327, 4552), (19717, 44324), (81306, 1342296), (88784, 2093195),
+              (410236, 2439437), (875713, 4322051), (1134890, 2987624)]
+    b = (0.65538, 1.67431e-5, -2.24342e-6, 0.63641)
+    got = [epp.epp_paper_linreg_group_size(v, e) for v, e in table3]
+    want = [max(1, int(b[0] + b[1] * v + b[2] * e + b[3] * e / v + 0.5)) for v, e in table3]
+    assert got == want == [2, 2, 2, 10, 12, 6, 9, 15]
+    # far outside the fitted domain the value clamps to 1 (e.g. a path of configuration 4)
+    assert epp.epp_paper_linreg_group_size(2_449_029, 61_900_000) == 1

@@ -200,3 +200,19 @@ def test_export_is_unchanged_by_aggregation_and_hot_cold_marking(monkeypatch):
         Xp[sets_o[1] == 0] = np.nan
         assert_close(run_partial(p, Xp), want, f"hot budget {mb} MB, nan-poison")
         assert_paths_bit_exact(paths, sets_o, paths_o, 2)
+
+
+def test_deep_model_shares_the_saturated_path():
+    """Once N^{k+1} == N^k every deeper layer has the same execution path: it is built once."""
+    n = 40
+    g = graphgen.csr_from_edges(n, [(i, (i + 1) % n) for i in range(n)], self_loops=True)
+    L = n // 2 + 4
+    paths = check_layers(g, [0], L, [5] * L, 90)
+    handles = [paths.path(l)._h for l in range(L)]
+    # N^20 = N^21 = ... = V: level 20 (layer 3) is built, levels 21..23 (layers 2, 1, 0) share it
+    assert handles[0] == handles[1] == handles[2] == handles[3]
+    assert len(set(handles)) == L - 3
+    # without self-loops the sets alternate and never reach a fixed point: nothing is shared
+    g2 = graphgen.csr_from_edges(n, [(i, (i + 1) % n) for i in range(n)], self_loops=False, normalise=False)
+    paths2 = check_layers(g2, [0], 6, [3] * 6, 91)
+    assert len({paths2.path(l)._h for l in range(6)}) == 6
