@@ -240,6 +240,12 @@ def main():
         result["speedup_partial_over_all_active"] = ms_full / ms_partial if ms_partial > 0 else None
         saved = ms_full - ms_partial
         result["break_even_epochs"] = prepare_ms / saved if saved > 0 else None
+        # if-else selective scheduling on the whole graph (the paper's straightforward alternative)
+        ms_ie, ie_layer_ms = timed(lambda l: epp.epp_ifelse_aggregate(full, paths, l, grad_in[l], grad_out[l]), k_full,
+                                   min(args.warmup, 2))
+        result["if_else"] = {"ms_per_epoch": ms_ie, "steps": k_full,
+                             "layers": [{"l": l, "F": cfg.widths[l], "ms": ie_layer_ms[l]} for l in order]}
+        result["speedup_partial_over_if_else"] = ms_ie / ms_partial if ms_partial > 0 else None
 
     if not args.no_cpu_baseline:
         del grad_out

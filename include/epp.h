@@ -128,6 +128,16 @@ int epp_backward_aggregate(epp_path_t* p, const float* grad_in, float* grad_out,
  * every one of the n rows of grad_out (rows with empty lists become zero). */
 int epp_full_aggregate(epp_path_t* full, const float* grad_in, float* grad_out, int F, epp_stream_t stream);
 
+/* If-else selective scheduling (Sec. 4, the first straightforward alternative; comparison
+ * baseline of Fig. 6): the all-active kernel on the whole input graph with an "is this vertex
+ * active" test on every row (is v in N^{L-l}?) and every neighbour (is u in N^{L-l-1}?), using
+ * the membership bitmaps kept in `paths`.  Same result and output contract as
+ * epp_backward_aggregate(epp_get_path(paths, l), ...): rows of N^{L-l} are overwritten, all
+ * other rows untouched, inactive source rows are never read.  The whole edge array of the
+ * graph is still traversed. */
+int epp_ifelse_aggregate(epp_path_t* full, const epp_paths_t* paths, int l, const float* grad_in, float* grad_out,
+                         int F, epp_stream_t stream);
+
 void epp_destroy_paths(epp_paths_t* p);
 void epp_destroy_path(epp_path_t* p); /* only for handles from epp_prepare_full */
 

@@ -26,7 +26,7 @@ EXPORTED = [
     "epp_prepare", "epp_prepare_full", "epp_num_layers", "epp_get_path", "epp_path_info",
     "epp_path_export", "epp_active_set_export", "epp_select_group_size", "epp_path_set_group_size",
     "epp_backward_aggregate", "epp_full_aggregate", "epp_destroy_paths", "epp_destroy_path",
-    "epp_last_error", "epp_paper_linreg_group_size",
+    "epp_last_error", "epp_paper_linreg_group_size", "epp_ifelse_aggregate",
 ]
 
 
@@ -73,6 +73,7 @@ def load_library() -> ctypes.CDLL:
     lib.epp_paper_linreg_group_size.argtypes = [I64, I64]
     lib.epp_backward_aggregate.argtypes = [P, P, P, I, P]
     lib.epp_full_aggregate.argtypes = [P, P, P, I, P]
+    lib.epp_ifelse_aggregate.argtypes = [P, P, I, P, P, I, P]
     lib.epp_destroy_paths.argtypes = [P]
     lib.epp_destroy_paths.restype = None
     lib.epp_destroy_path.argtypes = [P]
@@ -228,3 +229,10 @@ def epp_backward_aggregate(path: Path_, grad_in: torch.Tensor, grad_out: torch.T
 def epp_full_aggregate(full: Path_, grad_in: torch.Tensor, grad_out: torch.Tensor) -> None:
     F = _grads(full, grad_in, grad_out)
     _check(load_library().epp_full_aggregate(full._h, grad_in.data_ptr(), grad_out.data_ptr(), F, _stream()))
+
+
+def epp_ifelse_aggregate(full: Path_, paths: Paths, l: int, grad_in: torch.Tensor, grad_out: torch.Tensor) -> None:
+    """If-else selective scheduling baseline (Sec. 4): all-active traversal with activity tests."""
+    F = _grads(full, grad_in, grad_out)
+    _check(load_library().epp_ifelse_aggregate(full._h, paths._h, l, grad_in.data_ptr(), grad_out.data_ptr(), F,
+                                               _stream()))

@@ -72,6 +72,7 @@ __global__ __launch_bounds__(kBlock) void k_sched_groups(const int32_t* __restri
 // indices) or, for the all-active graph, the vertices whose lists are empty.
 __global__ __launch_bounds__(kBlock) void k_zero_rows(const int32_t* __restrict__ rows, int64_t n_rows,
                                                       const int32_t* __restrict__ row_ids, int F,
+                                                      const unsigned int* __restrict__ only_bits,
                                                       float* __restrict__ out) {
     int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (i >= n_rows * F) return;
@@ -79,6 +80,7 @@ __global__ __launch_bounds__(kBlock) void k_zero_rows(const int32_t* __restrict_
     int f = (int)(i - r * F);
     int32_t v = rows[r];
     if (row_ids) v = row_ids[v];
+    if (only_bits && !((only_bits[v >> 5] >> (v & 31)) & 1u)) return;
     out[(size_t)v * F + f] = 0.0f;
 }
 
@@ -93,6 +95,9 @@ struct AggArgs {
     int F;
     int gs;
     int log2ns;                // feature slices spread over the XCDs (1 << log2ns of them)
+    // if-else selective scheduling only: membership bitmaps of the layer's rows and sources
+    const unsigned int* row_bits;
+    const unsigned int* src_bits;
 };
 
 template <int VEC>
@@ -121,7 +126,7 @@ __device__ __forceinline__ void write_row(float* __restrict__ o, const float (&a
 // The next 4T pairs are fetched into registers while the current ones are consumed.  The
 // staging area is private to the wavefront (LDS operations of one wavefront execute in
 // order), so no workgroup barrier is involved.
-template <int VEC, int LOG2T, int U_>
+template <int VEC, int LOG2T, int U_, bool IFELSE>
 __global__ __launch_bounds__(kBlock) void k_aggregate(AggArgs a) {
     constexpr int T = 1 << LOG2T;
     constexpr int S = 4 * T;              // pairs staged per slot
@@ -167,6 +172,20 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(AggArgs a) {
             if (j >= len) { pre[i].x &= kColMask; pre[i].y = 0; }
         }
         for (int base = 0; base < len; base += S) {
+            if constexpr (IFELSE) {
+                // "is this neighbour active" test of selective scheduling, done for the 4T pairs
+                // of a stage at once; inactive neighbours keep their flags but lose their column
+                // (no valid id has all 30 bits set), so that the gather below skips them
+                bool act[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int c = pre[i].x & kColMask;
+                    act[i] = (a.src_bits[c >> 5] >> (c & 31)) & 1u;
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (!act[i]) { pre[i].x |= kColMask; pre[i].y = 0; }
+            }
             __builtin_amdgcn_wave_barrier();
 #pragma unroll
             for (int i = 0; i < 4; ++i) stage[i * T + t] = pre[i];
@@ -187,9 +206,15 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(AggArgs a) {
                 vec_t x[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) e[u] = stage[b + u];
+                bool act[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    if (fok) {
+                    act[u] = fok;
+                    if constexpr (IFELSE) act[u] = fok && ((e[u].x & kColMask) != kColMask);
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (act[u]) {
                         int c = e[u].x & kColMask;
                         if (e[u].x & kCold) {
                             // rarely referenced source: streamed, so that it does not evict hot rows from
@@ -212,7 +237,9 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(AggArgs a) {
                     const int j = base + b + u;
                     if (j < len) open = true;
                     if (e[u].x < 0) {  // last entry of row r
-                        if (fok) write_row<VEC>(dstbase + (size_t)v * (size_t)a.F, acc, shared);
+                        bool wr = fok;
+                        if constexpr (IFELSE) wr = fok && ((a.row_bits[v >> 5] >> (v & 31)) & 1u);
+                        if (wr) write_row<VEC>(dstbase + (size_t)v * (size_t)a.F, acc, shared);
 #pragma unroll
                         for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
                         shared = false;
@@ -225,7 +252,11 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(AggArgs a) {
             }
         }
         // the group ends inside a row: that row continues in the next group
-        if (open && fok) write_row<VEC>(dstbase + (size_t)v * (size_t)a.F, acc, true);
+        if (open && fok) {
+            bool wr = true;
+            if constexpr (IFELSE) wr = (a.row_bits[v >> 5] >> (v & 31)) & 1u;
+            if (wr) write_row<VEC>(dstbase + (size_t)v * (size_t)a.F, acc, true);
+        }
     }
 }
 
@@ -257,7 +288,8 @@ void launch_one(hipStream_t s, const AggArgs& a) {
     const int64_t blocks_per_slice = (a.n_groups + per_block - 1) / per_block;
     const int64_t xcds_per_slice = 8 >> a.log2ns;
     const int64_t q = (blocks_per_slice + xcds_per_slice - 1) / xcds_per_slice;
-    hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U>), dim3((unsigned)(q * 8)), dim3(kBlock), 0, s, a);
+    if (a.row_bits) hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, true>), dim3((unsigned)(q * 8)), dim3(kBlock), 0, s, a);
+    else hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, false>), dim3((unsigned)(q * 8)), dim3(kBlock), 0, s, a);
 }
 
 template <int VEC, int U>
@@ -370,7 +402,8 @@ int epp_build_schedule(epp_path* p, int gs, hipStream_t s, Schedule** out) {
     return EPP_OK;
 }
 
-int epp_launch_aggregate(epp_path* p, Schedule* sc, const float* in, float* out, int F, hipStream_t s) {
+int epp_launch_aggregate(epp_path* p, Schedule* sc, const float* in, float* out, int F, hipStream_t s,
+                         const unsigned int* row_bits, const unsigned int* src_bits) {
     int vec, log2T;
     const bool aligned16 = ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & 15) == 0;
     row_shape(F, aligned16, &vec, &log2T);
@@ -382,12 +415,13 @@ int epp_launch_aggregate(epp_path* p, Schedule* sc, const float* in, float* out,
     if (sc->n_split_rows > 0) {
         const int64_t total = sc->n_split_rows * F;
         hipLaunchKernelGGL(k_zero_rows, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
-                           sc->cut_rows.as<int32_t>(), sc->n_split_rows, row_ids, F, out);
+                           sc->cut_rows.as<int32_t>(), sc->n_split_rows, row_ids, F, row_bits, out);
     }
-    if (p->n_empty_rows > 0) {  // all-active graph: vertices without any entry become zero
+    if (p->n_empty_rows > 0 && !row_bits) {  // all-active graph: vertices without any entry become zero
         const int64_t total = p->n_empty_rows * F;
         hipLaunchKernelGGL(k_zero_rows, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
-                           p->empty_rows.as<int32_t>(), p->n_empty_rows, (const int32_t*)nullptr, F, out);
+                           p->empty_rows.as<int32_t>(), p->n_empty_rows, (const int32_t*)nullptr, F,
+                           (const unsigned int*)nullptr, out);
     }
     if (sc->n_groups > 0) {
         AggArgs a;
@@ -401,6 +435,8 @@ int epp_launch_aggregate(epp_path* p, Schedule* sc, const float* in, float* out,
         a.F = F;
         a.gs = sc->gs;
         a.log2ns = log2ns;
+        a.row_bits = row_bits;
+        a.src_bits = src_bits;
         // gathers in flight per lane: 8 x 16 bytes, or 16 narrower ones
         if (vec == 4) launch_vec<4, 8>(log2T, s, a);
         else if (vec == 2) launch_vec<2, 16>(log2T, s, a);

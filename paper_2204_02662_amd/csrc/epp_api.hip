@@ -36,14 +36,15 @@ int ensure_schedule(epp_path* p, int F, hipStream_t s, epp_path::WidthCfg** out)
     return EPP_OK;
 }
 
-int aggregate(epp_path* p, const float* in, float* out, int F, hipStream_t s) {
+int aggregate(epp_path* p, const float* in, float* out, int F, hipStream_t s, const unsigned int* row_bits = nullptr,
+              const unsigned int* src_bits = nullptr) {
     if (!p || !in || !out) { epp_set_error("NULL argument"); return EPP_ERR_INVALID_ARG; }
     if (F < 1) { epp_set_error("F must be >= 1 (got %d)", F); return EPP_ERR_INVALID_ARG; }
     if ((int64_t)p->n * F >= (1ll << 40)) { epp_set_error("gradient matrix too large"); return EPP_ERR_TOO_LARGE; }
     if (in == out) { epp_set_error("grad_in and grad_out must not alias"); return EPP_ERR_INVALID_ARG; }
     epp_path::WidthCfg* w = nullptr;
     EPP_TRY(ensure_schedule(p, F, s, &w));
-    return epp_launch_aggregate(p, w->sched, in, out, F, s);
+    return epp_launch_aggregate(p, w->sched, in, out, F, s, row_bits, src_bits);
 }
 
 }  // namespace
@@ -124,4 +125,15 @@ extern "C" int epp_full_aggregate(epp_path_t* full, const float* grad_in, float*
         return EPP_ERR_INVALID_ARG;
     }
     return aggregate(full, grad_in, grad_out, F, (hipStream_t)stream);
+}
+
+extern "C" int epp_ifelse_aggregate(epp_path_t* full, const epp_paths_t* paths, int l, const float* grad_in,
+                                    float* grad_out, int F, epp_stream_t stream) {
+    if (!full || !paths) { epp_set_error("NULL argument"); return EPP_ERR_INVALID_ARG; }
+    if (!full->all_rows) { epp_set_error("epp_ifelse_aggregate needs a handle from epp_prepare_full"); return EPP_ERR_INVALID_ARG; }
+    if (l < 0 || l >= paths->L) { epp_set_error("no such layer"); return EPP_ERR_INVALID_ARG; }
+    if (full->n != paths->n) { epp_set_error("handles belong to different graphs"); return EPP_ERR_INVALID_ARG; }
+    const int k = paths->L - 1 - l;  // rows N^{k+1}, sources N^k
+    return aggregate(full, grad_in, grad_out, F, (hipStream_t)stream, paths->bitmaps[k + 1].as<unsigned int>(),
+                     paths->bitmaps[k].as<unsigned int>());
 }

@@ -121,6 +121,7 @@ int epp_path_finish(epp_path* p, hipStream_t s);  // histogram + max length of a
 
 // aggregate.hip
 int epp_build_schedule(epp_path* p, int gs, hipStream_t s, Schedule** out);
-int epp_launch_aggregate(epp_path* p, Schedule* sc, const float* in, float* out, int F, hipStream_t s);
+int epp_launch_aggregate(epp_path* p, Schedule* sc, const float* in, float* out, int F, hipStream_t s,
+                         const unsigned int* row_bits = nullptr, const unsigned int* src_bits = nullptr);
 int epp_default_group_size(const epp_path* p, int F);
 int epp_mark_cold_sources(epp_path* p, int F, hipStream_t s);

@@ -81,3 +81,13 @@ def run_full(full, X: np.ndarray) -> np.ndarray:
     epp.epp_full_aggregate(full, gin, gout)
     torch.cuda.synchronize()
     return gout.cpu().numpy()
+
+
+def run_ifelse(full, paths, l, X: np.ndarray, poison: float = 123.0) -> np.ndarray:
+    """If-else selective scheduling baseline; grad_out starts at `poison`."""
+    d = dev()
+    gin = torch.from_numpy(X).to(d)
+    gout = torch.full_like(gin, poison)
+    epp.epp_ifelse_aggregate(full, paths, l, gin, gout)
+    torch.cuda.synchronize()
+    return gout.cpu().numpy()

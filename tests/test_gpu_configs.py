@@ -82,4 +82,11 @@ def test_large_config(k):
         got2 = gout2.cpu().numpy()
         assert np.isfinite(got2).all()
         assert_close(got2[sample], want[sample], f"cfg {k} layer {l} nan-poison")
-        del gin, gout, gout2, got, got2, X
+        # if-else selective scheduling baseline on the NaN-poisoned input: same rows, same values
+        gout3 = torch.full_like(gin, 77.0)
+        epp.epp_ifelse_aggregate(full, paths, l, gin, gout3)
+        torch.cuda.synchronize()
+        got3 = gout3.cpu().numpy()
+        assert np.all(got3[~rows] == 77.0)
+        assert_close(got3[sample], want[sample], f"cfg {k} layer {l} if-else")
+        del gin, gout, gout2, gout3, got, got2, got3, X

@@ -17,7 +17,7 @@ pytestmark = [pytest.mark.gpu,
 if torch.cuda.is_available():
     import paper_2204_02662_amd as epp
     from _util import (assert_close, assert_paths_bit_exact, gpu_prepare, gpu_prepare_full, run_full, run_partial,
-                       dev)
+                       run_ifelse, dev)
 
 
 def oprep(g, train, L):
@@ -52,6 +52,13 @@ def check_layers(g, train, L, widths, seed, gs_list=(0,)):
         assert_close(run_partial(p, Xp), want, f"nan-poison l={l}")
         # the all-active kernel gives the same matrix (Theorem 1) and writes every row
         assert_close(run_full(full, X), oracle.full_aggregate(g.n, g.rowptr, g.col, g.val, X), f"full l={l}")
+        # if-else selective scheduling on the whole graph: same rows written, same values,
+        # inactive sources never read
+        rows = sets_o[L - l].astype(bool)
+        for Xi in (X, Xp):
+            got = run_ifelse(full, paths, l, Xi)
+            assert np.all(got[~rows] == 123.0)
+            assert_close(got[rows], want[rows], f"if-else l={l}")
     return paths
 
 
