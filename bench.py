@@ -247,6 +247,21 @@ def main():
                              "layers": [{"l": l, "F": cfg.widths[l], "ms": ie_layer_ms[l]} for l in order]}
         result["speedup_partial_over_if_else"] = ms_ie / ms_partial if ms_partial > 0 else None
 
+    # launch-bound workloads: the same epoch captured once in a HIP graph and replayed
+    if ms_partial < 1.0 and not args.layers:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for l in order:
+                epp.epp_backward_aggregate(path_objs[l], grad_in[l], grad_out[l])
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        result["partially_active"]["hip_graph_ms_per_epoch"] = (time.perf_counter() - t) * 1e3 / args.steps
+
     if not args.no_cpu_baseline:
         del grad_out
         torch.cuda.empty_cache()

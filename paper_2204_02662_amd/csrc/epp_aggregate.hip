@@ -88,6 +88,7 @@ struct AggArgs {
     const int2v* cv;           // (column | row-end flag, weight bits) per entry
     const int32_t* group_row;  // per group: first row (bit 31: starts inside that row)
     const int32_t* row_ids;    // streamed row -> vertex; NULL: identity
+    int64_t n_rows;            // streamed rows
     const float* in;
     float* out;
     int64_t nnz;
@@ -133,7 +134,11 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(AggArgs a) {
     constexpr int U = U_ < S ? U_ : S;    // S is a multiple of U
     typedef typename VecT<VEC>::type vec_t;
     __shared__ int2v stage_all[kBlock / 64][64 * 4];
+    __shared__ int32_t ids_all[kBlock / 64][64];
     int2v* __restrict__ stage = stage_all[threadIdx.x >> 6] + (((threadIdx.x & 63) >> LOG2T) * S);
+    // vertex ids of the slot's next T rows, streamed through LDS like the pairs (rows are
+    // consumed in order, so one coalesced load serves T row ends)
+    int32_t* __restrict__ ids = ids_all[threadIdx.x >> 6] + (((threadIdx.x & 63) >> LOG2T) * T);
 
     // XCD-aware mapping.  Workgroups are dealt round-robin to the 8 XCDs (each with its own
     // L2).  With ns > 1 feature slices, XCD x works on slice x % ns of every row only, so its
@@ -156,14 +161,8 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(AggArgs a) {
         const bool fok = f < a.F;
         const float* __restrict__ src = a.in + (fok ? f : 0);
         float* __restrict__ dstbase = a.out + f;
-        int r = gr & 0x7FFFFFFF;
-        bool shared = gr < 0;  // the current row is shared with the previous group
-        int32_t v = (a.row_ids && has) ? a.row_ids[r] : r;
-        float acc[VEC];
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
-        bool open = false;  // acc holds entries of a row whose end has not been met
-
+        // first 4T pairs of the group: issued before anything that depends on the group table,
+        // so that the two load chains (pairs -> gathers, group row -> vertex id) overlap
         int2v pre[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -171,6 +170,25 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(AggArgs a) {
             pre[i] = len > 0 ? __builtin_nontemporal_load(my + std::min(j, len - 1)) : int2v{0, 0};
             if (j >= len) { pre[i].x &= kColMask; pre[i].y = 0; }
         }
+        int r = gr & 0x7FFFFFFF;
+        bool shared = gr < 0;  // the current row is shared with the previous group
+        const int64_t r_last = a.n_rows - 1;
+        int id_base = r;        // ids[] holds the vertices of rows id_base .. id_base + T - 1
+        int32_t id_pre = 0;     // lane's share of the following T rows, already in flight
+        int32_t v = r;
+        if (a.row_ids) {
+            const int32_t mine = has ? a.row_ids[std::min<int64_t>((int64_t)r + t, r_last)] : 0;
+            id_pre = has ? a.row_ids[std::min<int64_t>((int64_t)r + T + t, r_last)] : 0;
+            __builtin_amdgcn_wave_barrier();
+            ids[t] = mine;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            v = ids[0];
+        }
+        float acc[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
+        bool open = false;  // acc holds entries of a row whose end has not been met
         for (int base = 0; base < len; base += S) {
             if constexpr (IFELSE) {
                 // "is this neighbour active" test of selective scheduling, done for the 4T pairs
@@ -245,8 +263,19 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(AggArgs a) {
                         shared = false;
                         open = false;
                         ++r;
-                        // vertex of the next row; the very last entry of the path has no successor
-                        if (!a.row_ids) v = r; else if (j0 + j + 1 < a.nnz) v = a.row_ids[r];
+                        if (!a.row_ids) {
+                            v = r;
+                        } else {
+                            if (r - id_base == T) {  // the T staged ids are used up: switch to the next T
+                                id_base = r;
+                                __builtin_amdgcn_wave_barrier();
+                                ids[t] = id_pre;
+                                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                                __builtin_amdgcn_wave_barrier();
+                                id_pre = a.row_ids[std::min<int64_t>((int64_t)r + T + t, r_last)];
+                            }
+                            v = ids[r - id_base];
+                        }
                     }
                 }
             }
@@ -428,6 +457,7 @@ int epp_launch_aggregate(epp_path* p, Schedule* sc, const float* in, float* out,
         a.cv = reinterpret_cast<const int2v*>(p->cv.p);
         a.group_row = sc->group_row.as<int32_t>();
         a.row_ids = row_ids;
+        a.n_rows = p->n_stream_rows;
         a.in = in;
         a.out = out;
         a.nnz = p->nnz;

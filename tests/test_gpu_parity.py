@@ -223,3 +223,41 @@ def test_deep_model_shares_the_saturated_path():
     g2 = graphgen.csr_from_edges(n, [(i, (i + 1) % n) for i in range(n)], self_loops=False, normalise=False)
     paths2 = check_layers(g2, [0], 6, [3] * 6, 91)
     assert len({paths2.path(l)._h for l in range(6)}) == 6
+
+
+def test_epoch_captured_in_a_hip_graph_replays_correctly():
+    """After the first (schedule-building) call the aggregate entry points only enqueue
+    kernels, so a whole epoch can be captured in a HIP graph; every replay must reproduce the
+    eager result (split rows are re-zeroed by a kernel inside the graph)."""
+    cfg = graphgen.make_config(1)
+    g, L = cfg.graph, cfg.L
+    sets_o, paths_o = oprep(g, cfg.train_ids, L)
+    paths = gpu_prepare(g, cfg.train_ids, L)
+    d = dev()
+    xs = [torch.from_numpy(graphgen.layer_gradient(cfg, l, sets_o[L - l - 1])).to(d) for l in range(L)]
+    ys = [torch.zeros_like(x) for x in xs]
+    ps = [paths.path(l) for l in range(L)]
+    want = [oracle.path_aggregate(g.n, paths_o[l], xs[l].cpu().numpy()) for l in range(L)]
+
+    def epoch():
+        for l in range(L - 1, -1, -1):
+            epp.epp_backward_aggregate(ps[l], xs[l], ys[l])
+
+    epoch()  # builds the schedules (allocates, synchronises): must happen before capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        epoch()
+    for rep in range(4):
+        for y in ys:
+            y.normal_()          # eager work between replays; rows of the path must be overwritten
+        rows = [torch.from_numpy(sets_o[L - l].astype(bool)).to(d) for l in range(L)]
+        keep = [ys[l][~rows[l]].clone() for l in range(L)]
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for l in range(L):
+            got = ys[l].cpu().numpy()
+            r = sets_o[L - l].astype(bool)
+            assert_close(got[r], want[l][r], f"replay {rep} layer {l}")
+            assert torch.equal(ys[l][~rows[l]], keep[l])  # rows outside the path untouched
