@@ -96,6 +96,7 @@ struct AggArgs {
     int F;
     int gs;
     int log2ns;                // feature slices spread over the XCDs (1 << log2ns of them)
+    int has_cold;              // some entries carry the cold flag (host-side kernel choice)
     // if-else selective scheduling only: membership bitmaps of the layer's rows and sources
     const unsigned int* row_bits;
     const unsigned int* src_bits;
@@ -127,7 +128,7 @@ __device__ __forceinline__ void write_row(float* __restrict__ o, const float (&a
 // The next 4T pairs are fetched into registers while the current ones are consumed.  The
 // staging area is private to the wavefront (LDS operations of one wavefront execute in
 // order), so no workgroup barrier is involved.
-template <int VEC, int LOG2T, int U_, bool IFELSE>
+template <int VEC, int LOG2T, int U_, bool IFELSE, bool COLD>
 __global__ __launch_bounds__(kBlock) void k_aggregate(AggArgs a) {
     constexpr int T = 1 << LOG2T;
     constexpr int S = 4 * T;              // pairs staged per slot
@@ -234,7 +235,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(AggArgs a) {
                 for (int u = 0; u < U; ++u) {
                     if (act[u]) {
                         int c = e[u].x & kColMask;
-                        if (e[u].x & kCold) {
+                        if (COLD && (e[u].x & kCold)) {
                             // rarely referenced source: streamed, so that it does not evict hot rows from
                             // L2 and the memory-side cache (the index is laundered so that the two loads
                             // stay two instructions, each with its own cache policy)
@@ -317,8 +318,14 @@ void launch_one(hipStream_t s, const AggArgs& a) {
     const int64_t blocks_per_slice = (a.n_groups + per_block - 1) / per_block;
     const int64_t xcds_per_slice = 8 >> a.log2ns;
     const int64_t q = (blocks_per_slice + xcds_per_slice - 1) / xcds_per_slice;
-    if (a.row_bits) hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, true>), dim3((unsigned)(q * 8)), dim3(kBlock), 0, s, a);
-    else hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, false>), dim3((unsigned)(q * 8)), dim3(kBlock), 0, s, a);
+    const dim3 grid((unsigned)(q * 8)), block(kBlock);
+    if (a.row_bits) {
+        if (a.has_cold) hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, true, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, true, false>), grid, block, 0, s, a);
+    } else {
+        if (a.has_cold) hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, false, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, false, false>), grid, block, 0, s, a);
+    }
 }
 
 template <int VEC, int U>
@@ -406,7 +413,6 @@ int epp_build_schedule(epp_path* p, int gs, hipStream_t s, Schedule** out) {
     Schedule* sc = new Schedule();
     struct Guard { Schedule* s; ~Guard() { delete s; } } guard{sc};
     sc->gs = gs;
-    sc->log2_slices = env_int("EPP_TUNE_LOG2_SLICES", 0);
     const int64_t n_groups = (p->nnz + gs - 1) / gs;
     if (n_groups >= 0x7FFFFFFFll) { epp_set_error("too many groups"); return EPP_ERR_TOO_LARGE; }
     sc->n_groups = n_groups;
@@ -431,13 +437,13 @@ int epp_build_schedule(epp_path* p, int gs, hipStream_t s, Schedule** out) {
     return EPP_OK;
 }
 
-int epp_launch_aggregate(epp_path* p, Schedule* sc, const float* in, float* out, int F, hipStream_t s,
+int epp_launch_aggregate(epp_path* p, Schedule* sc, int log2_slices, const float* in, float* out, int F, hipStream_t s,
                          const unsigned int* row_bits, const unsigned int* src_bits) {
     int vec, log2T;
     const bool aligned16 = ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & 15) == 0;
     row_shape(F, aligned16, &vec, &log2T);
     // feature slices over the XCDs: each slice keeps whole 128-byte lines of a row
-    int log2ns = std::min(std::max(sc->log2_slices, 0), 3);
+    int log2ns = std::min(std::max(log2_slices, 0), 3);
     while (log2ns > 0 && ((log2T - log2ns) < 0 || ((vec * 4) << (log2T - log2ns)) < 128)) --log2ns;
     log2T -= log2ns;
     const int32_t* row_ids = p->row_ids.p ? p->row_ids.as<int32_t>() : nullptr;
@@ -465,6 +471,7 @@ int epp_launch_aggregate(epp_path* p, Schedule* sc, const float* in, float* out,
         a.F = F;
         a.gs = sc->gs;
         a.log2ns = log2ns;
+        a.has_cold = p->cold_thr > 0;
         a.row_bits = row_bits;
         a.src_bits = src_bits;
         // gathers in flight per lane: 8 x 16 bytes, or 16 narrower ones
@@ -476,17 +483,29 @@ int epp_launch_aggregate(epp_path* p, Schedule* sc, const float* in, float* out,
     return EPP_OK;
 }
 
-// Which sources are worth caching.  The gathered rows of a big path do not fit the caches
-// (4 MB L2 per XCD, 256 MB memory-side cache); with plain loads the rarely referenced rows
-// keep evicting the often referenced ones.  Sources are ranked by how often the path
-// references them; the most referenced ones, as many as fit the budget, stay "hot", all
-// entries of the others get the cold flag and are gathered with streaming loads.
-int epp_mark_cold_sources(epp_path* p, int F, hipStream_t s) {
+// Cache-locality choices of one (path, width), made from how often the path references each
+// source.
+//
+// Hot / cold sources.  The gathered rows of a big path do not fit the caches (4 MB L2 per
+// XCD, 256 MB memory-side cache); with plain loads the rarely referenced rows keep evicting
+// the often referenced ones.  The most referenced sources, as many as fit the budget, stay
+// "hot"; all entries of the others get the cold flag and are gathered with streaming loads.
+//
+// XCD feature slicing.  Two slices double the number of distinct rows an L2 can hold at the
+// price of reading the index stream twice and of touching twice as many rows per gather
+// instruction.  It pays when the hottest sources carry much of the traffic: it is switched on
+// when rows are at least 512 bytes and the sources that fit with slicing, but not without,
+// receive at least 6 % of all references (measured: R-MAT configuration, 8 % -> 16.5 to 15.3
+// ms; Chung-Lu configuration, 4 % -> 4.3 to 4.6 ms, left off).
+int epp_tune_locality(epp_path* p, int F, hipStream_t s, int* log2_slices) {
     const int64_t budget_mb = env_int("EPP_TUNE_HOT_MB", 96);
     const int64_t rows_budget = budget_mb * (1ll << 20) / ((int64_t)F * 4);
+    const int forced_slices = env_int("EPP_TUNE_LOG2_SLICES", -1);
+    *log2_slices = forced_slices >= 0 ? forced_slices : 0;
     int thr = 0;
     DevBuf cnt;
-    if (budget_mb > 0 && p->nnz > 0 && p->n_src > rows_budget) {
+    // (measured useful for rows of 256 bytes and more; at F = 47 the extra branch costs 3 %)
+    if (budget_mb > 0 && p->nnz > 0 && p->n_src > rows_budget && (int64_t)F * 4 >= 256) {
         EPP_TRY(cnt.alloc((size_t)p->n * 4));
         EPP_HIP_TRY(hipMemsetAsync(cnt.p, 0, cnt.bytes, s));
         DevBuf hist;
@@ -509,6 +528,20 @@ int epp_mark_cold_sources(epp_path* p, int F, hipStream_t s) {
         }
         // bins 1..c are cold
         thr = c < 1 ? 0 : bin_floor(c + 1 == 4 ? 8 : c + 1);
+
+        if (forced_slices < 0 && (int64_t)F * 4 >= 512) {
+            // share of the references that goes to the sources ranked (rows one L2 holds) ..
+            // (twice that), estimated from the bins (a bin's sources count as its lower bound)
+            const int64_t l2_rows = (4ll << 20) / ((int64_t)F * 4);
+            double refs_between = 0.0;
+            int64_t rank = 0;
+            for (int b = kCountBins - 1; b >= 1; --b) {
+                const int64_t lo = std::max(rank, l2_rows), hi = std::min<int64_t>(rank + (int64_t)h[b], 2 * l2_rows);
+                if (hi > lo) refs_between += (double)(hi - lo) * (double)bin_floor(b);
+                rank += (int64_t)h[b];
+            }
+            if (refs_between >= 0.06 * (double)p->nnz) *log2_slices = 1;
+        }
     }
     if (thr == p->cold_thr) return EPP_OK;
     hipLaunchKernelGGL(k_mark_cold, dim3((unsigned)((p->nnz + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,

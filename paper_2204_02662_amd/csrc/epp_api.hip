@@ -12,7 +12,7 @@ thread_local char g_err[512] = "";
 epp_path::WidthCfg* width_cfg(epp_path* p, int F) {
     for (auto& w : p->widths)
         if (w.F == F) return &w;
-    p->widths.push_back(epp_path::WidthCfg{F, 0, nullptr});
+    p->widths.push_back(epp_path::WidthCfg{F, 0, nullptr, 0});
     return &p->widths.back();
 }
 
@@ -28,7 +28,7 @@ int ensure_schedule(epp_path* p, int F, hipStream_t s, epp_path::WidthCfg** out)
         const int gs = w->forced_gs > 0 ? w->forced_gs : epp_default_group_size(p, F);
         Schedule* sc = find_schedule(p, gs);
         if (!sc) EPP_TRY(epp_build_schedule(p, gs, s, &sc));
-        EPP_TRY(epp_mark_cold_sources(p, F, s));
+        EPP_TRY(epp_tune_locality(p, F, s, &w->log2_slices));
         w->sched = sc;
     }
     p->last_F = F;
@@ -44,7 +44,7 @@ int aggregate(epp_path* p, const float* in, float* out, int F, hipStream_t s, co
     if (in == out) { epp_set_error("grad_in and grad_out must not alias"); return EPP_ERR_INVALID_ARG; }
     epp_path::WidthCfg* w = nullptr;
     EPP_TRY(ensure_schedule(p, F, s, &w));
-    return epp_launch_aggregate(p, w->sched, in, out, F, s, row_bits, src_bits);
+    return epp_launch_aggregate(p, w->sched, w->log2_slices, in, out, F, s, row_bits, src_bits);
 }
 
 }  // namespace

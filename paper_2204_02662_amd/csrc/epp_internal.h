@@ -67,7 +67,6 @@ struct DevBuf {
 // [g * gs, min((g + 1) * gs, nnz)).
 struct Schedule {
     int gs = 0;
-    int log2_slices = 0;       // feature slices spread over the XCDs (request; clipped per width)
     int64_t n_groups = 0;
     int64_t n_split_rows = 0;  // rows cut by a group boundary (written with atomics)
     DevBuf group_row;          // int32[n_groups] row holding the group's first entry; bit 31: starts inside it
@@ -95,7 +94,7 @@ struct epp_path {
     DevBuf empty_rows;           // int32[n_empty_rows] vertices with empty lists
     std::vector<Schedule*> scheds;
     // per-width choices
-    struct WidthCfg { int F; int forced_gs; Schedule* sched; };
+    struct WidthCfg { int F; int forced_gs; Schedule* sched; int log2_slices; };  // slices: XCD feature slicing
     std::vector<WidthCfg> widths;
     int last_F = 0;
     ~epp_path() { for (Schedule* s : scheds) delete s; }
@@ -121,7 +120,7 @@ int epp_path_finish(epp_path* p, hipStream_t s);  // histogram + max length of a
 
 // aggregate.hip
 int epp_build_schedule(epp_path* p, int gs, hipStream_t s, Schedule** out);
-int epp_launch_aggregate(epp_path* p, Schedule* sc, const float* in, float* out, int F, hipStream_t s,
+int epp_launch_aggregate(epp_path* p, Schedule* sc, int log2_slices, const float* in, float* out, int F, hipStream_t s,
                          const unsigned int* row_bits = nullptr, const unsigned int* src_bits = nullptr);
 int epp_default_group_size(const epp_path* p, int F);
-int epp_mark_cold_sources(epp_path* p, int F, hipStream_t s);
+int epp_tune_locality(epp_path* p, int F, hipStream_t s, int* log2_slices);
