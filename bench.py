@@ -3,7 +3,10 @@
 
 A "step" is one epoch of backward aggregation: one launch of the partially-active kernel
 per layer, l = L-1 ... 0 (Alg. 2), over synthetic inputs that are already resident in HBM.
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric/value/unit (ms per epoch of the partially-active path), per-layer
+times with algorithmic bytes and roofline fractions, the dominant kernel's `roofline` object,
+the all-active and if-else comparisons, the one-off `prepare_ms`, and `cpu_baseline` (the CPU
+oracle timed on this machine's host cores).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--no-cpu-baseline]
 """
@@ -219,6 +222,9 @@ def main():
         "roofline": roofline,
         "partially_active": {"ms_per_epoch": ms_partial, "sum_layer_ms": sum(layer_ms.values()), "layers": layers},
         "prepare_ms": prepare_ms,
+        # one-off path construction: two passes over the column ids, one over the kept weights,
+        # the (col, val) pairs written once, row pointer read and filtered pointer written per level
+        "prepare_algorithmic_bytes": sum(8 * g.nnz + 12 * infos[l].nnz + 8 * (g.n + 1) for l in range(L)),
         # layers past the fixed point of the active sets share one path object: count it once
         "path_bytes_over_csr_bytes": sum({path_objs[l]._h: infos[l].bytes for l in range(L)}.values())
         / (8.0 * g.nnz + 4.0 * (g.n + 1)),

@@ -1,4 +1,4 @@
-"""Measurement studies around the hot path (run on a GPU machine):
+"""Measurement studies around the hot path (they need a GPU):
 
     python -m paper_2204_02662_amd.studies gs    --config 4          # group-size sweep per layer (Sec. 5, Fig. 4 analogue)
     python -m paper_2204_02662_amd.studies depth --config 4 --F 64   # L = 2..6 (multi-layer study, Fig. 10 analogue)
