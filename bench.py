@@ -186,6 +186,14 @@ def main():
                      for i, l in enumerate(order)}
         return wall_ms, per_layer
 
+    # the first call per (path, width) also builds the group table and the locality marks
+    torch.cuda.synchronize()
+    t = time.perf_counter()
+    for l in order:
+        epp.epp_backward_aggregate(path_objs[l], grad_in[l], grad_out[l])
+    torch.cuda.synchronize()
+    first_epoch_ms = (time.perf_counter() - t) * 1e3
+
     ms_partial, layer_ms = timed(lambda l: epp.epp_backward_aggregate(path_objs[l], grad_in[l], grad_out[l]),
                                  args.steps, args.warmup)
     for l in range(L):
@@ -222,9 +230,12 @@ def main():
         "roofline": roofline,
         "partially_active": {"ms_per_epoch": ms_partial, "sum_layer_ms": sum(layer_ms.values()), "layers": layers},
         "prepare_ms": prepare_ms,
+        "schedule_ms": max(first_epoch_ms - ms_partial, 0.0),  # one-off part of the first epoch
         # one-off path construction: two passes over the column ids, one over the kept weights,
         # the (col, val) pairs written once, row pointer read and filtered pointer written per level
-        "prepare_algorithmic_bytes": sum(8 * g.nnz + 12 * infos[l].nnz + 8 * (g.n + 1) for l in range(L)),
+        # (layers past the fixed point of the active sets are built once)
+        "prepare_algorithmic_bytes": sum(8 * g.nnz + 12 * nz + 8 * (g.n + 1)
+                                         for nz in {path_objs[l]._h: infos[l].nnz for l in range(L)}.values()),
         # layers past the fixed point of the active sets share one path object: count it once
         "path_bytes_over_csr_bytes": sum({path_objs[l]._h: infos[l].bytes for l in range(L)}.values())
         / (8.0 * g.nnz + 4.0 * (g.n + 1)),
@@ -245,7 +256,7 @@ def main():
         result["all_active"] = {"ms_per_epoch": ms_full, "steps": k_full, "layers": fl}
         result["speedup_partial_over_all_active"] = ms_full / ms_partial if ms_partial > 0 else None
         saved = ms_full - ms_partial
-        result["break_even_epochs"] = prepare_ms / saved if saved > 0 else None
+        result["break_even_epochs"] = (prepare_ms + result["schedule_ms"]) / saved if saved > 0 else None
         # if-else selective scheduling on the whole graph (the paper's straightforward alternative)
         ms_ie, ie_layer_ms = timed(lambda l: epp.epp_ifelse_aggregate(full, paths, l, grad_in[l], grad_out[l]), k_full,
                                    min(args.warmup, 2))

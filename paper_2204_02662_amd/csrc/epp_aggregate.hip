@@ -342,9 +342,13 @@ void launch_vec(int log2T, hipStream_t s, const AggArgs& a) {
 }
 
 // ---- hot / cold sources -----------------------------------------------------------------
-__global__ __launch_bounds__(kBlock) void k_count_sources(const int2v* __restrict__ cv, int64_t nnz,
+// Reference counts of the sources from a sample of the entries: every `stride`-th 64-entry
+// segment is counted (ranking the often referenced sources does not need exact counts, and a
+// full count means one atomic per entry, tens of thousands of them on the same hub address).
+__global__ __launch_bounds__(kBlock) void k_count_sources(const int2v* __restrict__ cv, int64_t nnz, int64_t stride,
                                                           int* __restrict__ cnt) {
-    int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int64_t seg = ((int64_t)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6)) * stride;
+    const int64_t e = seg * 64 + (threadIdx.x & 63);
     if (e < nnz) atomicAdd(&cnt[cv[e].x & kColMask], 1);
 }
 
@@ -368,21 +372,39 @@ __global__ __launch_bounds__(kBlock) void k_count_hist(const int* __restrict__ c
     if (threadIdx.x < kCountBins) h[threadIdx.x] = 0;
     __syncthreads();
     int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (v < n) {
-        int k = cnt[v];
-        if (k > 0) atomicAdd(&h[count_bin(k)], 1);
+    const int k = v < n ? cnt[v] : 0;
+    int bin = k > 0 ? count_bin(k) : -1;
+    // lanes with the same bin add once together (most lanes share a handful of small bins)
+    unsigned long long todo = __ballot(bin >= 0);
+    while (todo) {
+        const int leader = __ffsll((long long)todo) - 1;
+        const int b = __shfl(bin, leader, 64);
+        const unsigned long long same = __ballot(bin == b);
+        if ((threadIdx.x & 63) == leader) atomicAdd(&h[b], __popcll(same));
+        todo &= ~same;
     }
     __syncthreads();
     if (threadIdx.x < kCountBins && h[threadIdx.x]) atomicAdd(&hist[threadIdx.x], (unsigned long long)h[threadIdx.x]);
 }
 
-__global__ __launch_bounds__(kBlock) void k_mark_cold(int2v* __restrict__ cv, int64_t nnz, const int* __restrict__ cnt,
-                                                      int thr) {
+// One bit per vertex: referenced at least `thr` times in the sample.
+__global__ __launch_bounds__(kBlock) void k_hot_bitmap(const int* __restrict__ cnt, int64_t n, int thr,
+                                                       unsigned long long* __restrict__ bits) {
+    int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const unsigned long long b = __ballot(v < n && cnt[v] >= thr);
+    if ((threadIdx.x & 63) == 0 && (v >> 6) < ((n + 63) >> 6)) bits[v >> 6] = b;
+}
+
+// Set or clear the cold flag of every entry (hot == NULL: clear all).
+__global__ __launch_bounds__(kBlock) void k_mark_cold(int2v* __restrict__ cv, int64_t nnz,
+                                                      const unsigned int* __restrict__ hot) {
     int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (e >= nnz) return;
-    int x = cv[e].x & ~kCold;
-    if (cnt && cnt[x & kColMask] < thr) x |= kCold;
-    cv[e].x = x;
+    int2v x = cv[e];
+    x.x &= ~kCold;
+    const int c = x.x & kColMask;
+    if (hot && !((hot[c >> 5] >> (c & 31)) & 1u)) x.x |= kCold;
+    cv[e] = x;  // whole pairs: full-line writes
 }
 
 }  // namespace
@@ -511,8 +533,12 @@ int epp_tune_locality(epp_path* p, int F, hipStream_t s, int* log2_slices) {
         DevBuf hist;
         EPP_TRY(hist.alloc(kCountBins * sizeof(unsigned long long)));
         EPP_HIP_TRY(hipMemsetAsync(hist.p, 0, hist.bytes, s));
-        hipLaunchKernelGGL(k_count_sources, dim3((unsigned)((p->nnz + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
-                           reinterpret_cast<const int2v*>(p->cv.p), p->nnz, cnt.as<int>());
+        // at most ~16 M sampled entries
+        const int64_t n_seg = (p->nnz + 63) / 64;
+        const int64_t stride = std::max<int64_t>(1, n_seg / (1 << 18));
+        const int64_t n_sampled_seg = (n_seg + stride - 1) / stride;
+        hipLaunchKernelGGL(k_count_sources, dim3((unsigned)((n_sampled_seg + (kBlock / 64) - 1) / (kBlock / 64))),
+                           dim3(kBlock), 0, s, reinterpret_cast<const int2v*>(p->cv.p), p->nnz, stride, cnt.as<int>());
         hipLaunchKernelGGL(k_count_hist, dim3((unsigned)((p->n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
                            cnt.as<int>(), p->n, hist.as<unsigned long long>());
         EPP_HIP_TRY(hipGetLastError());
@@ -527,7 +553,7 @@ int epp_tune_locality(epp_path* p, int F, hipStream_t s, int* log2_slices) {
             kept += (int64_t)h[c];
         }
         // bins 1..c are cold
-        thr = c < 1 ? 0 : bin_floor(c + 1 == 4 ? 8 : c + 1);
+        thr = c < 1 ? 1 : bin_floor(c + 1 == 4 ? 8 : c + 1);  // sources the sample never met are cold
 
         if (forced_slices < 0 && (int64_t)F * 4 >= 512) {
             // share of the references that goes to the sources ranked (rows one L2 holds) ..
@@ -540,12 +566,18 @@ int epp_tune_locality(epp_path* p, int F, hipStream_t s, int* log2_slices) {
                 if (hi > lo) refs_between += (double)(hi - lo) * (double)bin_floor(b);
                 rank += (int64_t)h[b];
             }
-            if (refs_between >= 0.06 * (double)p->nnz) *log2_slices = 1;
+            if (refs_between >= 0.06 * (double)p->nnz / (double)stride) *log2_slices = 1;
         }
     }
     if (thr == p->cold_thr) return EPP_OK;
+    DevBuf hot;
+    if (thr > 0) {
+        EPP_TRY(hot.alloc((size_t)((p->n + 63) / 64) * 8));
+        hipLaunchKernelGGL(k_hot_bitmap, dim3((unsigned)((p->n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
+                           cnt.as<int>(), p->n, thr, hot.as<unsigned long long>());
+    }
     hipLaunchKernelGGL(k_mark_cold, dim3((unsigned)((p->nnz + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
-                       reinterpret_cast<int2v*>(p->cv.p), p->nnz, thr > 0 ? cnt.as<int>() : (const int*)nullptr, thr);
+                       reinterpret_cast<int2v*>(p->cv.p), p->nnz, thr > 0 ? hot.as<unsigned int>() : (const unsigned int*)nullptr);
     EPP_HIP_TRY(hipGetLastError());
     EPP_HIP_TRY(hipStreamSynchronize(s));
     p->cold_thr = thr;

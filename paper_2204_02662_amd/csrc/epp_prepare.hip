@@ -75,16 +75,24 @@ __global__ __launch_bounds__(kBlock) void k_edge_mask(const int32_t* __restrict_
     __shared__ int wave_cnt[4];
     const int wave = threadIdx.x >> 6, lane = lane_id();
     int cnt = 0;
-    for (int i = wave; i < kSegsPerTile; i += 4) {
-        int64_t seg = (int64_t)blockIdx.x * kSegsPerTile + i;
-        int64_t e = seg * 64 + lane;
-        bool keep = false;
-        if (e < nnz) {
-            int32_t c = col[e];
-            keep = (bitmap32[c >> 5] >> (c & 31)) & 1u;
-        }
-        unsigned long long m = __ballot(keep);
-        if (lane == 0 && seg < n_seg) mask[seg] = m;
+    // a wavefront owns 8 consecutive segments; all column loads, then all bitmap lookups, are
+    // issued back to back so that the two dependent memory latencies are paid once per tile
+    constexpr int kPerWave = kSegsPerTile / 4;
+    const int64_t seg0 = (int64_t)blockIdx.x * kSegsPerTile + wave * kPerWave;
+    int32_t c[kPerWave];
+    unsigned int w[kPerWave];
+#pragma unroll
+    for (int i = 0; i < kPerWave; ++i) {
+        const int64_t e = (seg0 + i) * 64 + lane;
+        c[i] = e < nnz ? col[e] : -1;
+    }
+#pragma unroll
+    for (int i = 0; i < kPerWave; ++i) w[i] = c[i] >= 0 ? bitmap32[c[i] >> 5] : 0u;
+#pragma unroll
+    for (int i = 0; i < kPerWave; ++i) {
+        const bool keep = c[i] >= 0 && ((w[i] >> (c[i] & 31)) & 1u);
+        const unsigned long long m = __ballot(keep);
+        if (lane == 0 && seg0 + i < n_seg) mask[seg0 + i] = m;
         cnt += __popcll(m);
     }
     if (lane == 0) wave_cnt[wave] = cnt;
@@ -138,14 +146,24 @@ __global__ __launch_bounds__(kBlock) void k_edge_extract(const int32_t* __restri
         }
     }
     __syncthreads();
-    for (int i = wave; i < kSegsPerTile; i += 4) {
-        int64_t seg = (int64_t)blockIdx.x * kSegsPerTile + i;
-        if (seg >= n_seg) break;
-        unsigned long long m = mask[seg];
-        if ((m >> lane) & 1ull) {
-            int64_t e = seg * 64 + lane;
-            int pos = sbase[i] + __popcll(m & low_mask(lane));
-            cv[pos] = make_int2(col[e], __float_as_int(val[e]));
+    constexpr int kPerWave = kSegsPerTile / 4;
+    unsigned long long m[kPerWave];
+    int2 x[kPerWave];
+#pragma unroll
+    for (int i = 0; i < kPerWave; ++i) {
+        const int64_t seg = (int64_t)blockIdx.x * kSegsPerTile + wave * kPerWave + i;
+        m[i] = seg < n_seg ? mask[seg] : 0ull;
+    }
+#pragma unroll
+    for (int i = 0; i < kPerWave; ++i) {
+        const int64_t e = ((int64_t)blockIdx.x * kSegsPerTile + wave * kPerWave + i) * 64 + lane;
+        if ((m[i] >> lane) & 1ull) x[i] = make_int2(col[e], __float_as_int(val[e]));
+    }
+#pragma unroll
+    for (int i = 0; i < kPerWave; ++i) {
+        if ((m[i] >> lane) & 1ull) {
+            const int pos = sbase[wave * kPerWave + i] + __popcll(m[i] & low_mask(lane));
+            cv[pos] = x[i];
         }
     }
 }
