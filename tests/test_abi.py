@@ -38,6 +38,16 @@ def test_host_side_argument_checks_need_no_gpu():
     out = ctypes.c_void_p()
     assert lib.epp_prepare(None, None, 0, 1, None, ctypes.byref(out)) == epp.EPP_ERR_INVALID_ARG
     assert lib.epp_select_group_size(None, 16) == epp.EPP_ERR_INVALID_ARG
+    # size limits are checked before anything is dereferenced or sent to the GPU
+    dummy = ctypes.c_void_p(16)
+    for n, nnz, want in ((1 << 30, 10, epp.EPP_ERR_TOO_LARGE), (10, (1 << 31) - 1, epp.EPP_ERR_TOO_LARGE),
+                         (-1, 0, epp.EPP_ERR_INVALID_ARG)):
+        csr = epp._Csr(n, nnz, dummy, dummy, dummy)
+        assert lib.epp_prepare(ctypes.byref(csr), None, 0, 2, None, ctypes.byref(out)) == want
+        assert lib.epp_prepare_full(ctypes.byref(csr), None, ctypes.byref(out)) == want
+    csr = epp._Csr(10, 10, dummy, dummy, dummy)
+    assert lib.epp_prepare(ctypes.byref(csr), None, 0, 0, None, ctypes.byref(out)) == epp.EPP_ERR_INVALID_ARG  # L < 1
+    assert lib.epp_prepare(ctypes.byref(csr), None, 5, 1, None, ctypes.byref(out)) == epp.EPP_ERR_INVALID_ARG  # ids NULL
 
 
 def test_paper_linear_regression_group_size():

@@ -261,3 +261,40 @@ def test_epoch_captured_in_a_hip_graph_replays_correctly():
             r = sets_o[L - l].astype(bool)
             assert_close(got[r], want[l][r], f"replay {rep} layer {l}")
             assert torch.equal(ys[l][~rows[l]], keep[l])  # rows outside the path untouched
+
+
+def test_randomised_shapes():
+    """Many small random problems: graph shape, direction, self-loops, depth, width, group size."""
+    rng = np.random.default_rng(2024)
+    for case in range(60):
+        n = int(rng.integers(1, 700))
+        m = int(rng.integers(0, 6 * n + 1))
+        sym = bool(rng.integers(0, 2))
+        loops = bool(rng.integers(0, 2))
+        edges = [(int(u), int(v)) for u, v in rng.integers(0, n, (m, 2)) if u != v]
+        if case % 7 == 0 and n > 3:  # a hub that gets cut into many groups
+            edges += [(0, int(v)) for v in range(1, n)]
+        g = graphgen.csr_from_edges(n, edges, self_loops=loops, symmetric=sym, normalise=sym)
+        if not sym:
+            g.val[:] = rng.uniform(-2.0, 2.0, g.nnz).astype(np.float32)
+        L = int(rng.integers(1, 5))
+        train = rng.choice(n, size=int(rng.integers(0, n + 1)), replace=True)
+        sets_o, paths_o = oprep(g, train, L)
+        paths = gpu_prepare(g, train, L)
+        assert_paths_bit_exact(paths, sets_o, paths_o, L)
+        full = gpu_prepare_full(g)
+        for l in range(L):
+            F = int(rng.choice([1, 2, 3, 4, 5, 8, 12, 16, 17, 33, 64, 65, 128, 129, 260]))
+            X = graphgen.normal_rows(g.n, F, sets_o[L - l - 1], 1000 + case)
+            want = oracle.path_aggregate(g.n, paths_o[l], X)
+            p = paths.path(l)
+            gs = int(rng.choice([0, 1, 2, 5, 7, 16, 40, 1000]))
+            p.set_group_size(F, gs)
+            rows = sets_o[L - l].astype(bool)
+            got = run_partial(p, X, poison=-7.0)
+            assert np.all(got[~rows] == -7.0), f"case {case} l={l}"
+            assert_close(got[rows], want[rows], f"case {case} l={l} F={F} gs={gs} n={n}")
+            assert_close(run_full(full, X), oracle.full_aggregate(g.n, g.rowptr, g.col, g.val, X), f"case {case} full")
+            ie = run_ifelse(full, paths, l, X)
+            assert np.all(ie[~rows] == 123.0)
+            assert_close(ie[rows], want[rows], f"case {case} l={l} if-else")
