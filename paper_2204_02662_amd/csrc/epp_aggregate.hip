@@ -134,6 +134,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(AggArgs a) {
     constexpr int S = 4 * T;              // pairs staged per slot
     constexpr int U = U_ < S ? U_ : S;    // S is a multiple of U
     typedef typename VecT<VEC>::type vec_t;
+    typedef __attribute__((address_space(1))) const vec_t* gvec_ptr;  // global memory, stated for the loads
     __shared__ int2v stage_all[kBlock / 64][64 * 4];
     __shared__ int32_t ids_all[kBlock / 64][64];
     int2v* __restrict__ stage = stage_all[threadIdx.x >> 6] + (((threadIdx.x & 63) >> LOG2T) * S);
@@ -164,13 +165,12 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(AggArgs a) {
         float* __restrict__ dstbase = a.out + f;
         // first 4T pairs of the group: issued before anything that depends on the group table,
         // so that the two load chains (pairs -> gathers, group row -> vertex id) overlap
+        // (pairs past the end of the group are clamped loads; they are neutralised only when they
+        // are parked in LDS, so that nothing waits on a load right after issuing it)
         int2v pre[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int j = i * T + t;
-            pre[i] = len > 0 ? __builtin_nontemporal_load(my + std::min(j, len - 1)) : int2v{0, 0};
-            if (j >= len) { pre[i].x &= kColMask; pre[i].y = 0; }
-        }
+        for (int i = 0; i < 4; ++i)
+            pre[i] = len > 0 ? __builtin_nontemporal_load(my + std::min(i * T + t, len - 1)) : int2v{0, 0};
         int r = gr & 0x7FFFFFFF;
         bool shared = gr < 0;  // the current row is shared with the previous group
         const int64_t r_last = a.n_rows - 1;
@@ -207,16 +207,16 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(AggArgs a) {
             }
             __builtin_amdgcn_wave_barrier();
 #pragma unroll
-            for (int i = 0; i < 4; ++i) stage[i * T + t] = pre[i];
+            for (int i = 0; i < 4; ++i) {
+                if (base + i * T + t >= len) { pre[i].x &= kColMask; pre[i].y = 0; }  // no row end, weight 0
+                stage[i * T + t] = pre[i];
+            }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             if (base + S < len) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int j = base + S + i * T + t;
-                    pre[i] = __builtin_nontemporal_load(my + std::min(j, len - 1));
-                    if (j >= len) { pre[i].x &= kColMask; pre[i].y = 0; }
-                }
+                for (int i = 0; i < 4; ++i)
+                    pre[i] = __builtin_nontemporal_load(my + std::min(base + S + i * T + t, len - 1));
             }
             const int n_here = std::min(S, len - base);
             for (int b = 0; b < n_here; b += U) {
@@ -225,34 +225,42 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(AggArgs a) {
                 vec_t x[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) e[u] = stage[b + u];
+                // (lanes past the last feature read feature 0 and never write: the loads stay
+                // unconditional, so that nothing but their own results is ever waited on)
                 bool act[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    act[u] = fok;
-                    if constexpr (IFELSE) act[u] = fok && ((e[u].x & kColMask) != kColMask);
+                    act[u] = true;
+                    if constexpr (IFELSE) act[u] = (e[u].x & kColMask) != kColMask;
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     if (act[u]) {
-                        int c = e[u].x & kColMask;
+                        const int c = e[u].x & kColMask;
+                        gvec_ptr p = (gvec_ptr)(src + (size_t)c * (size_t)a.F);
                         if (COLD && (e[u].x & kCold)) {
                             // rarely referenced source: streamed, so that it does not evict hot rows from
-                            // L2 and the memory-side cache (the index is laundered so that the two loads
-                            // stay two instructions, each with its own cache policy)
-                            asm volatile("" : "+v"(c));
-                            x[u] = __builtin_nontemporal_load(reinterpret_cast<const vec_t*>(src + (size_t)c * (size_t)a.F));
+                            // L2 and the memory-side cache.  (The address is laundered, and the branch
+                            // ends in an empty statement the other one lacks, so that the two loads stay
+                            // two instructions, each with its own cache policy.)
+                            asm volatile("" : "+v"(p));
+                            x[u] = __builtin_nontemporal_load(p);
+                            asm volatile("");
                         } else {
-                            x[u] = *reinterpret_cast<const vec_t*>(src + (size_t)c * (size_t)a.F);
+                            x[u] = *p;
                         }
-                    } else {
-                        x[u] = vec_t{};
+                        // the address stays live past both loads: a result register that overlapped it
+                        // would make the second load wait for the first
+                        if constexpr (COLD) asm volatile("" ::"v"(p));
                     }
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const float w = __int_as_float(e[u].y);
+                    if (act[u]) {  // (a skipped neighbour has no x[u]: nothing is zero-filled between loads)
 #pragma unroll
-                    for (int i = 0; i < VEC; ++i) acc[i] = fmaf(w, lane_get<VEC>(x[u], i), acc[i]);
+                        for (int i = 0; i < VEC; ++i) acc[i] = fmaf(w, lane_get<VEC>(x[u], i), acc[i]);
+                    }
                     const int j = base + b + u;
                     if (j < len) open = true;
                     if (e[u].x < 0) {  // last entry of row r
