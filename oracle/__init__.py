@@ -147,3 +147,48 @@ def partial_aggregate(n, rowptr, col, val, member_rows, member_src, grad_in) -> 
     lib.oracle_partial_aggregate(n, _p(rowptr), _p(col), _p(val), _p(member_rows), _p(member_src),
                                  _p(grad_in), _p(out), F)
     return out
+
+
+# ---------------------------------------------------------------------------------------
+# Combination stage of the backward pass (Alg. 1, backward loop: the two lines before the
+# aggregation loop).  Plain definitions in fp64; numpy's matrix product is the only library
+# step.  `member` restricts both products to the vertices whose rows of X^{(l+1)'} can be
+# non-zero (Theorem 1: N^{L-l-1}); with member=None every vertex takes part, which is the
+# definition itself.  Pinned by tests/test_oracle_combination.py (loop-by-loop brute force,
+# closed forms, the trace identity <W, W'> = <Y, Y'>, finite differences of the forward
+# model of Alg. 1, and restricted == unrestricted when the skipped rows are zero).
+
+def _members(n, member):
+    return np.arange(n) if member is None else np.flatnonzero(np.asarray(member))
+
+
+def weight_gradient(Y, grad_X, member=None):
+    """W' = Y^T (x) X'  (F_in x F_out), summed over the vertices of `member`.
+
+    Returns (W' in fp64, A) where A[i, j] = sum_v |Y[v, i]| |X'[v, j]| is the scale that
+    bounds the rounding error of any fp32 evaluation order."""
+    Y = np.asarray(Y)
+    grad_X = np.asarray(grad_X)
+    assert Y.shape[0] == grad_X.shape[0]
+    v = _members(Y.shape[0], member)
+    Yv = Y[v].astype(np.float64)
+    Xv = grad_X[v].astype(np.float64)
+    return Yv.T @ Xv, np.abs(Yv).T @ np.abs(Xv)
+
+
+def input_gradient(grad_X, W, member=None):
+    """Y' = X' (x) W^T  (N x F_in); rows outside `member` are zero.
+
+    Returns (Y' rounded once to fp32, A) with A[v, i] = sum_j |X'[v, j]| |W[i, j]|."""
+    grad_X = np.asarray(grad_X)
+    W = np.asarray(W)
+    assert grad_X.shape[1] == W.shape[1]
+    n = grad_X.shape[0]
+    v = _members(n, member)
+    out = np.zeros((n, W.shape[0]), np.float64)
+    scale = np.zeros((n, W.shape[0]), np.float64)
+    Xv = grad_X[v].astype(np.float64)
+    Wd = W.astype(np.float64)
+    out[v] = Xv @ Wd.T
+    scale[v] = np.abs(Xv) @ np.abs(Wd).T
+    return out.astype(np.float32), scale
