@@ -138,6 +138,29 @@ int epp_full_aggregate(epp_path_t* full, const float* grad_in, float* grad_out, 
 int epp_ifelse_aggregate(epp_path_t* full, const epp_paths_t* paths, int l, const float* grad_in, float* grad_out,
                          int F, epp_stream_t stream);
 
+/* Combination stage of the backward pass restricted to the active rows (Alg. 1, backward
+ * loop: W'(l) = Y(l)^T (x) X'(l+1) and Y'(l) = X'(l+1) (x) W(l)^T; by Theorem 1 the rows of
+ * X'(l+1) outside N^k, k = L-l-1, are zero and add nothing to either product).  Both run on
+ * the matrix cores in fp32.
+ *   k        which active set holds the non-zero rows of grad_X: 0..L, or -1 for all n rows
+ *            (the unrestricted products)
+ *   Y        device, n x F_in   forward aggregation result of the layer
+ *   grad_X   device, n x F_out  rows outside N^k are never read
+ *   W        device, F_in x F_out row-major
+ *   grad_W   device, F_in x F_out, overwritten (all zeros when N^k is empty)
+ *   grad_Y   device, n x F_in: rows of N^k are overwritten, all others are not touched (they are
+ *            the rows that epp_backward_aggregate never reads)
+ *   workspace  device scratch of at least epp_weight_gradient_workspace(...) bytes, 16-byte
+ *            aligned, owned by the caller; holds partial sums over blocks of rows that a second
+ *            kernel adds in a fixed order (results do not depend on timing)
+ * 1 <= F_in, F_out <= 4096.  Asynchronous on `stream` (the first use of k = 0 builds the id
+ * list of N^0 and synchronises once).  Matrices must not alias. */
+int64_t epp_weight_gradient_workspace(const epp_paths_t* paths, int k, int F_in, int F_out); /* bytes, < 0: error */
+int epp_weight_gradient(epp_paths_t* paths, int k, const float* Y, int F_in, const float* grad_X, int F_out,
+                        float* grad_W, void* workspace, int64_t workspace_bytes, epp_stream_t stream);
+int epp_input_gradient(epp_paths_t* paths, int k, const float* grad_X, int F_out, const float* W, int F_in,
+                       float* grad_Y, epp_stream_t stream);
+
 void epp_destroy_paths(epp_paths_t* p);
 void epp_destroy_path(epp_path_t* p); /* only for handles from epp_prepare_full */
 

@@ -27,6 +27,7 @@ EXPORTED = [
     "epp_path_export", "epp_active_set_export", "epp_select_group_size", "epp_path_set_group_size",
     "epp_backward_aggregate", "epp_full_aggregate", "epp_destroy_paths", "epp_destroy_path",
     "epp_last_error", "epp_paper_linreg_group_size", "epp_ifelse_aggregate",
+    "epp_weight_gradient_workspace", "epp_weight_gradient", "epp_input_gradient",
 ]
 
 
@@ -74,6 +75,10 @@ def load_library() -> ctypes.CDLL:
     lib.epp_backward_aggregate.argtypes = [P, P, P, I, P]
     lib.epp_full_aggregate.argtypes = [P, P, P, I, P]
     lib.epp_ifelse_aggregate.argtypes = [P, P, I, P, P, I, P]
+    lib.epp_weight_gradient_workspace.argtypes = [P, I, I, I]
+    lib.epp_weight_gradient_workspace.restype = I64
+    lib.epp_weight_gradient.argtypes = [P, I, P, I, P, I, P, P, I64, P]
+    lib.epp_input_gradient.argtypes = [P, I, P, I, P, I, P, P]
     lib.epp_destroy_paths.argtypes = [P]
     lib.epp_destroy_paths.restype = None
     lib.epp_destroy_path.argtypes = [P]
@@ -170,6 +175,11 @@ class Paths:
     def num_layers(self) -> int:
         return _check(load_library().epp_num_layers(self._h))
 
+    @property
+    def n(self) -> int:
+        """Vertices of the input graph."""
+        return self.path(0).info().n
+
     def path(self, l: int) -> Path_:
         h = load_library().epp_get_path(self._h, l)
         if not h:
@@ -236,3 +246,36 @@ def epp_ifelse_aggregate(full: Path_, paths: Paths, l: int, grad_in: torch.Tenso
     F = _grads(full, grad_in, grad_out)
     _check(load_library().epp_ifelse_aggregate(full._h, paths._h, l, grad_in.data_ptr(), grad_out.data_ptr(), F,
                                                _stream()))
+
+
+def _matrix(t: torch.Tensor, what: str) -> torch.Tensor:
+    _dev(t, torch.float32)
+    if t.dim() != 2:
+        raise ValueError(f"{what} must be a matrix")
+    return t
+
+
+def epp_weight_gradient_workspace(paths: Paths, k: int, F_in: int, F_out: int) -> int:
+    return _check(load_library().epp_weight_gradient_workspace(paths._h, k, F_in, F_out))
+
+
+def epp_weight_gradient(paths: Paths, k: int, Y: torch.Tensor, grad_X: torch.Tensor, grad_W: torch.Tensor,
+                        workspace: torch.Tensor) -> None:
+    """W' = Y^T (x) X' over the rows of N^k (k = -1: all rows); `workspace` is a CUDA uint8 tensor of
+    at least epp_weight_gradient_workspace(...) bytes."""
+    _matrix(Y, "Y"), _matrix(grad_X, "grad_X"), _matrix(grad_W, "grad_W")
+    if Y.shape[0] != paths.n or grad_X.shape[0] != paths.n or grad_W.shape != (Y.shape[1], grad_X.shape[1]):
+        raise ValueError("shapes: Y n x F_in, grad_X n x F_out, grad_W F_in x F_out")
+    if not workspace.is_cuda or workspace.dtype != torch.uint8 or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous CUDA uint8 tensor")
+    _check(load_library().epp_weight_gradient(paths._h, k, Y.data_ptr(), Y.shape[1], grad_X.data_ptr(), grad_X.shape[1],
+                                              grad_W.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()))
+
+
+def epp_input_gradient(paths: Paths, k: int, grad_X: torch.Tensor, W: torch.Tensor, grad_Y: torch.Tensor) -> None:
+    """Y' = X' (x) W^T on the rows of N^k (k = -1: all rows); other rows of grad_Y are not touched."""
+    _matrix(grad_X, "grad_X"), _matrix(W, "W"), _matrix(grad_Y, "grad_Y")
+    if grad_X.shape[0] != paths.n or W.shape[1] != grad_X.shape[1] or grad_Y.shape != (grad_X.shape[0], W.shape[0]):
+        raise ValueError("shapes: grad_X n x F_out, W F_in x F_out, grad_Y n x F_in")
+    _check(load_library().epp_input_gradient(paths._h, k, grad_X.data_ptr(), grad_X.shape[1], W.data_ptr(), W.shape[0],
+                                             grad_Y.data_ptr(), _stream()))

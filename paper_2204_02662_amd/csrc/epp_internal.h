@@ -106,6 +106,8 @@ struct epp_paths {
     std::vector<DevBuf> bitmaps;    // L+1 bitmaps of N^k, uint64 words
     std::vector<int64_t> set_size;  // |N^k|
     std::vector<epp_path*> path;    // index l; once the sets stop growing, deeper layers share one object
+    DevBuf set0_ids;                // ascending ids of N^0, built on first use (the other sets are path rows)
+    bool have_set0_ids = false;
     ~epp_paths() {
         for (size_t i = 0; i < path.size(); ++i) {
             bool seen = false;
@@ -117,6 +119,8 @@ struct epp_paths {
 
 // prepare.hip
 int epp_path_finish(epp_path* p, hipStream_t s);  // histogram + max length of a built path
+// ascending vertex ids of N^k (device, owned by `p`); the first call for k = 0 synchronises
+int epp_active_ids(epp_paths* p, int k, hipStream_t s, const int32_t** ids, int64_t* count);
 
 // aggregate.hip
 int epp_build_schedule(epp_path* p, int gs, hipStream_t s, Schedule** out);

@@ -624,5 +624,30 @@ extern "C" int epp_active_set_export(const epp_paths_t* p, int k, int32_t* ids, 
     return EPP_OK;
 }
 
+int epp_active_ids(epp_paths* p, int k, hipStream_t s, const int32_t** ids, int64_t* count) {
+    if (k < 0 || k > p->L) { epp_set_error("k=%d outside [0, %d]", k, p->L); return EPP_ERR_INVALID_ARG; }
+    *count = p->set_size[k];
+    if (k > 0) {  // N^k is the row set of SG_{L-k}
+        *ids = p->path[p->L - k]->row_ids.as<int32_t>();
+        return EPP_OK;
+    }
+    if (!p->have_set0_ids) {
+        HostScalars hs;
+        EPP_TRY(hs.init());
+        DevBuf tile_cnt, tile_base, dev_total;
+        const size_t tiles = std::max<size_t>(grid_for((p->n + 63) / 64, kWordsPerTile), 1);
+        EPP_TRY(tile_cnt.alloc(tiles * 4));
+        EPP_TRY(tile_base.alloc(tiles * 4));
+        EPP_TRY(dev_total.alloc(sizeof(long long)));
+        int64_t c = 0;
+        EPP_TRY(compact_bitmap(p->bitmaps[0], p->n, nullptr, 0, &p->set0_ids, nullptr, &c, tile_cnt, tile_base,
+                               dev_total, hs, s));
+        EPP_HIP_TRY(hipStreamSynchronize(s));
+        p->have_set0_ids = true;
+    }
+    *ids = p->set0_ids.as<int32_t>();
+    return EPP_OK;
+}
+
 extern "C" void epp_destroy_paths(epp_paths_t* p) { delete p; }
 extern "C" void epp_destroy_path(epp_path_t* p) { delete p; }
