@@ -5,8 +5,10 @@
 // list of N^k only: the rows are gathered (and, for Y', scattered) by vertex id, everything
 // else is a dense contraction and runs on the matrix cores in fp32 (v_mfma_f32_32x32x2_f32).
 //
-// Both kernels are 64 x 64 output tiles per workgroup, four wavefronts in a 2 x 2 arrangement
-// with one 32 x 32 accumulator block each, and a contraction step of 32 staged through LDS.
+// Both kernels give a workgroup of four wavefronts (2 x 2) an output tile of 64 BM x 64 BN,
+// every wavefront BM x BN accumulator blocks of 32 x 32, and step through the contraction 32
+// at a time: the operand tiles of the next step are fetched into registers while the matrix
+// cores work on the current ones in LDS.
 //
 // Operand layout of the 32x32x2 instruction: lane l supplies A[l % 32][l / 32] and
 // B[l / 32][l % 32]; element j of its accumulator is C[8 (j / 4) + 4 (l / 32) + j % 4][l % 32].
@@ -20,111 +22,213 @@ namespace {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kBlock = 256;
-constexpr int kTile = 64;   // output tile edge
 constexpr int kStep = 32;   // contraction step
 constexpr int kMaxWidth = 4096;
+constexpr int kMinChunkRows = 256;
 
-// Y'[id, n] = sum_k X'[id, k] W[n, k] for the ids of one 64-row tile and 64 columns n.
+typedef float float4v __attribute__((ext_vector_type(4)));
+
+// Four consecutive floats of a row; VEC: one 16-byte access (the caller has checked that widths
+// are multiples of four and bases 16-byte aligned), else element by element up to `valid`.
+template <bool VEC>
+__device__ __forceinline__ float4v load4(const float* __restrict__ p, int valid) {
+    if constexpr (VEC) {
+        return valid > 0 ? *reinterpret_cast<const float4v*>(p) : float4v{0.f, 0.f, 0.f, 0.f};
+    } else {
+        float4v v = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (i < valid) v[i] = p[i];
+        return v;
+    }
+}
+
+// Thread mapping of all tile loads: eight threads per row, four consecutive floats each, so a
+// row segment of 32 floats is one 128-byte access and a thread needs one vertex id per row.
+
+// Y'[id, n] = sum_k X'[id, k] W[n, k] for the ids of one tile of 128 rows and 64 BN columns n.
+template <int BN, bool VEC>
 __global__ __launch_bounds__(kBlock) void k_input_gradient(const int32_t* __restrict__ ids, int64_t n_rows,
                                                            const float* __restrict__ G, int Fo,
                                                            const float* __restrict__ W, int Fi,
                                                            float* __restrict__ Yg) {
-    __shared__ float As[kTile][kStep + 1];   // X' rows of the tile, [row][k]
-    __shared__ float Bs[kStep][kTile + 1];   // W^T, [k][n]
-    __shared__ int64_t sid[kTile];           // vertex of each tile row, -1 past the end
+    constexpr int BM = 2, TM = 64 * BM, TN = 64 * BN;
+    constexpr int NA = TM / 32, NB = TN / 32;  // rows per thread and step
+    __shared__ float As[TM][kStep + 1];   // X' rows of the tile, [row][k]
+    __shared__ float Bs[kStep][TN + 1];   // W^T, [k][n]
+    __shared__ int64_t sid[TM];           // vertex of each tile row, -1 past the end
     const int t = threadIdx.x, lane = t & 63, w = t >> 6;
     const int wm = w & 1, wn = w >> 1;
-    const int64_t row0 = (int64_t)blockIdx.x * kTile;
-    const int n0 = blockIdx.y * kTile;
-    if (t < kTile) {
-        const int64_t r = row0 + t;
-        sid[t] = r < n_rows ? (ids ? (int64_t)ids[r] : r) : -1;
+    const int64_t row0 = (int64_t)blockIdx.x * TM;
+    const int n0 = blockIdx.y * TN;
+    for (int r = t; r < TM; r += kBlock) {
+        const int64_t row = row0 + r;
+        sid[r] = row < n_rows ? (ids ? (int64_t)ids[row] : row) : -1;
     }
     __syncthreads();
-    floatx16 acc = {};
+    const int tr = t >> 3, k = 4 * (t & 7);
+    const float* pa[NA];
+    const float* pb[NB];
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+        const int64_t id = sid[tr + 32 * i];
+        pa[i] = id >= 0 ? G + id * Fo + k : nullptr;
+    }
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        const int n = n0 + tr + 32 * i;
+        pb[i] = n < Fi ? W + (int64_t)n * Fo + k : nullptr;
+    }
+    float4v ra[NA], rb[NB];
+    auto fetch = [&](int k0) {
+        const int valid = Fo - (k0 + k);
+#pragma unroll
+        for (int i = 0; i < NA; ++i) ra[i] = load4<VEC>(pa[i] + k0, pa[i] ? valid : 0);
+#pragma unroll
+        for (int i = 0; i < NB; ++i) rb[i] = load4<VEC>(pb[i] + k0, pb[i] ? valid : 0);
+    };
+    floatx16 acc[BM][BN] = {};
+    fetch(0);
     for (int k0 = 0; k0 < Fo; k0 += kStep) {
 #pragma unroll
-        for (int i = 0; i < (kTile * kStep) / kBlock; ++i) {
-            const int e = t + kBlock * i;
-            const int r = e / kStep, k = e % kStep;
-            const int64_t id = sid[r];
-            As[r][k] = (id >= 0 && k0 + k < Fo) ? G[id * Fo + k0 + k] : 0.0f;
-            const int n = n0 + r;  // the same split serves the 64 x 32 block of W
-            Bs[k][r] = (n < Fi && k0 + k < Fo) ? W[(int64_t)n * Fo + k0 + k] : 0.0f;
-        }
+        for (int i = 0; i < NA; ++i)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) As[tr + 32 * i][k + c] = ra[i][c];
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) Bs[k + c][tr + 32 * i] = rb[i][c];
         __syncthreads();
+        if (k0 + kStep < Fo) fetch(k0 + kStep);
 #pragma unroll
         for (int kk = 0; kk < kStep; kk += 2) {
-            const float a = As[32 * wm + (lane & 31)][kk + (lane >> 5)];
-            const float b = Bs[kk + (lane >> 5)][32 * wn + (lane & 31)];
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+            float a[BM], b[BN];
+#pragma unroll
+            for (int bm = 0; bm < BM; ++bm) a[bm] = As[32 * (BM * wm + bm) + (lane & 31)][kk + (lane >> 5)];
+#pragma unroll
+            for (int bn = 0; bn < BN; ++bn) b[bn] = Bs[kk + (lane >> 5)][32 * (BN * wn + bn) + (lane & 31)];
+#pragma unroll
+            for (int bm = 0; bm < BM; ++bm)
+#pragma unroll
+                for (int bn = 0; bn < BN; ++bn)
+                    acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[bm], b[bn], acc[bm][bn], 0, 0, 0);
         }
         __syncthreads();
     }
-    const int n = n0 + 32 * wn + (lane & 31);
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-        const int i = 8 * (j / 4) + 4 * (lane >> 5) + (j % 4);
-        const int64_t id = sid[32 * wm + i];
-        if (id >= 0 && n < Fi) Yg[id * Fi + n] = acc[j];
-    }
+    for (int bm = 0; bm < BM; ++bm)
+#pragma unroll
+        for (int bn = 0; bn < BN; ++bn) {
+            const int n = n0 + 32 * (BN * wn + bn) + (lane & 31);
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const int i = 8 * (j / 4) + 4 * (lane >> 5) + (j % 4);
+                const int64_t id = sid[32 * (BM * wm + bm) + i];
+                if (id >= 0 && n < Fi) Yg[id * Fi + n] = acc[bm][bn][j];
+            }
+        }
 }
 
-// partial[chunk][m][n] = sum over the chunk's rows of Y[id, m] X'[id, n], one 64 x 64 tile.
+// partial[chunk][m][n] = sum over the chunk's rows of Y[id, m] X'[id, n], one tile of 64 BM x 64 BN.
+// The vertex id of a row is fetched one step before the row itself, so that the row loads of a
+// step never wait for an id.
+template <int BM, int BN, bool VEC>
 __global__ __launch_bounds__(kBlock) void k_weight_gradient(const int32_t* __restrict__ ids, int64_t n_rows,
                                                             int64_t rows_per_chunk, const float* __restrict__ Y,
                                                             int Fi, const float* __restrict__ G, int Fo,
                                                             float* __restrict__ partial) {
-    __shared__ float As[kStep][kTile];   // Y rows, [row][m]
-    __shared__ float Bs[kStep][kTile];   // X' rows, [row][n]
-    __shared__ int64_t sid[kStep];
+    constexpr int TM = 64 * BM, TN = 64 * BN;
+    constexpr int NA = TM / 32, NB = TN / 32;  // 4-float pieces per thread and step
+    __shared__ __attribute__((aligned(16))) float As[kStep][TM];   // Y rows, [row][m]
+    __shared__ __attribute__((aligned(16))) float Bs[kStep][TN];   // X' rows, [row][n]
     const int t = threadIdx.x, lane = t & 63, w = t >> 6;
     const int wm = w & 1, wn = w >> 1;
-    const int m0 = blockIdx.y * kTile, n0 = blockIdx.z * kTile;
+    const int m0 = blockIdx.y * TM, n0 = blockIdx.z * TN;
     const int64_t first = (int64_t)blockIdx.x * rows_per_chunk;
     const int64_t last = std::min<int64_t>(first + rows_per_chunk, n_rows);
-    floatx16 acc = {};
-    for (int64_t r0 = first; r0 < last; r0 += kStep) {
-        if (t < kStep) {
-            const int64_t r = r0 + t;
-            sid[t] = r < last ? (ids ? (int64_t)ids[r] : r) : -1;
-        }
-        __syncthreads();
+    const int tr = t >> 3, c4 = 4 * (t & 7);
+    auto vertex = [&](int64_t r) -> int64_t { return r < last ? (ids ? (int64_t)ids[r] : r) : -1; };
+    float4v ra[NA], rb[NB];
+    auto fetch = [&](int64_t id) {
+        const float* y = Y + id * Fi + m0 + c4;
+        const float* g = G + id * Fo + n0 + c4;
 #pragma unroll
-        for (int i = 0; i < (kStep * kTile) / kBlock; ++i) {
-            const int e = t + kBlock * i;
-            const int k = e / kTile, c = e % kTile;
-            const int64_t id = sid[k];
-            As[k][c] = (id >= 0 && m0 + c < Fi) ? Y[id * Fi + m0 + c] : 0.0f;
-            Bs[k][c] = (id >= 0 && n0 + c < Fo) ? G[id * Fo + n0 + c] : 0.0f;
-        }
+        for (int i = 0; i < NA; ++i) ra[i] = load4<VEC>(y + 32 * i, id >= 0 ? Fi - (m0 + c4 + 32 * i) : 0);
+#pragma unroll
+        for (int i = 0; i < NB; ++i) rb[i] = load4<VEC>(g + 32 * i, id >= 0 ? Fo - (n0 + c4 + 32 * i) : 0);
+    };
+    floatx16 acc[BM][BN] = {};
+    int64_t id_next = -1;
+    if (first < last) {
+        fetch(vertex(first + tr));
+        id_next = vertex(first + kStep + tr);
+    }
+    for (int64_t r0 = first; r0 < last; r0 += kStep) {
+#pragma unroll
+        for (int i = 0; i < NA; ++i) *reinterpret_cast<float4v*>(&As[tr][c4 + 32 * i]) = ra[i];
+#pragma unroll
+        for (int i = 0; i < NB; ++i) *reinterpret_cast<float4v*>(&Bs[tr][c4 + 32 * i]) = rb[i];
         __syncthreads();
+        if (r0 + kStep < last) {
+            fetch(id_next);
+            id_next = vertex(r0 + 2 * kStep + tr);
+        }
 #pragma unroll
         for (int kk = 0; kk < kStep; kk += 2) {
-            const float a = As[kk + (lane >> 5)][32 * wm + (lane & 31)];
-            const float b = Bs[kk + (lane >> 5)][32 * wn + (lane & 31)];
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+            float a[BM], b[BN];
+#pragma unroll
+            for (int bm = 0; bm < BM; ++bm) a[bm] = As[kk + (lane >> 5)][32 * (BM * wm + bm) + (lane & 31)];
+#pragma unroll
+            for (int bn = 0; bn < BN; ++bn) b[bn] = Bs[kk + (lane >> 5)][32 * (BN * wn + bn) + (lane & 31)];
+#pragma unroll
+            for (int bm = 0; bm < BM; ++bm)
+#pragma unroll
+                for (int bn = 0; bn < BN; ++bn)
+                    acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[bm], b[bn], acc[bm][bn], 0, 0, 0);
         }
         __syncthreads();
     }
-    const int n = n0 + 32 * wn + (lane & 31);
     float* __restrict__ mine = partial + (int64_t)blockIdx.x * Fi * Fo;
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-        const int m = m0 + 32 * wm + 8 * (j / 4) + 4 * (lane >> 5) + (j % 4);
-        if (m < Fi && n < Fo) mine[(int64_t)m * Fo + n] = acc[j];
+    for (int bm = 0; bm < BM; ++bm)
+#pragma unroll
+        for (int bn = 0; bn < BN; ++bn) {
+            const int n = n0 + 32 * (BN * wn + bn) + (lane & 31);
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const int m = m0 + 32 * (BM * wm + bm) + 8 * (j / 4) + 4 * (lane >> 5) + (j % 4);
+                if (m < Fi && n < Fo) mine[(int64_t)m * Fo + n] = acc[bm][bn][j];
+            }
+        }
+}
+
+// W'[e] = sum over chunks: 16 threads per element take every 16th chunk each, accumulate in
+// double, and are added in lane order (the result does not depend on timing).
+__global__ __launch_bounds__(kBlock) void k_weight_gradient_reduce(const float* __restrict__ partial, int64_t n_chunks,
+                                                                   int64_t total, float* __restrict__ Wg) {
+    __shared__ double part[16][17];
+    const int el = threadIdx.x & 15, cl = threadIdx.x >> 4;
+    const int64_t e = (int64_t)blockIdx.x * 16 + el;
+    double s = 0.0;
+    if (e < total)
+        for (int64_t c = cl; c < n_chunks; c += 16) s += (double)partial[c * total + e];
+    part[cl][el] = s;
+    __syncthreads();
+    if (cl == 0 && e < total) {
+        double sum = 0.0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sum += part[i][el];
+        Wg[e] = (float)sum;
     }
 }
 
-// W'[e] = sum over chunks, in chunk order, accumulated in double.
-__global__ __launch_bounds__(kBlock) void k_weight_gradient_reduce(const float* __restrict__ partial, int64_t n_chunks,
-                                                                   int64_t total, float* __restrict__ Wg) {
-    const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (e >= total) return;
-    double s = 0.0;
-    for (int64_t c = 0; c < n_chunks; ++c) s += (double)partial[c * total + e];
-    Wg[e] = (float)s;
+// 16-byte row accesses need widths that are multiples of four and aligned bases.
+bool aligned4(int Fa, int Fb, const void* a, const void* b) {
+    return Fa % 4 == 0 && Fb % 4 == 0 && ((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b)) & 15) == 0;
 }
+
+// Tile of the two launches: 128 wide where the matrix is, 64 otherwise.
+int blocks_for(int extent) { return extent > 64 ? 2 : 1; }
 
 int check_widths(int Fi, int Fo) {
     if (Fi < 1 || Fo < 1 || Fi > kMaxWidth || Fo > kMaxWidth) {
@@ -146,10 +250,11 @@ int row_set(epp_paths* p, int k, hipStream_t s, const int32_t** ids, int64_t* co
 
 // Rows per partial sum: enough chunks to fill the chip a few times over, whole steps each.
 void chunking(int64_t n_rows, int Fi, int Fo, int64_t* rows_per_chunk, int64_t* n_chunks) {
-    const int64_t tiles = (int64_t)((Fi + kTile - 1) / kTile) * ((Fo + kTile - 1) / kTile);
+    const int tm = 64 * blocks_for(Fi), tn = 64 * blocks_for(Fo);
+    const int64_t tiles = (int64_t)((Fi + tm - 1) / tm) * ((Fo + tn - 1) / tn);
     const int64_t want = std::max<int64_t>(1, 2048 / tiles);
-    int64_t per = (n_rows + want - 1) / want;
-    per = std::max<int64_t>(kStep, (per + kStep - 1) / kStep * kStep);
+    int64_t per = std::max<int64_t>((n_rows + want - 1) / want, kMinChunkRows);
+    per = (per + kStep - 1) / kStep * kStep;
     *rows_per_chunk = per;
     *n_chunks = (n_rows + per - 1) / per;
 }
@@ -182,12 +287,28 @@ extern "C" int epp_weight_gradient(epp_paths_t* paths, int k, const float* Y, in
     int64_t per, chunks;
     chunking(n_rows, F_in, F_out, &per, &chunks);
     if (chunks > 0) {
-        const dim3 grid((unsigned)chunks, (unsigned)((F_in + kTile - 1) / kTile), (unsigned)((F_out + kTile - 1) / kTile));
-        hipLaunchKernelGGL(k_weight_gradient, grid, dim3(kBlock), 0, s, ids, n_rows, per, Y, F_in, grad_X, F_out,
-                           static_cast<float*>(workspace));
+        const int bm = blocks_for(F_in), bn = blocks_for(F_out);
+        const dim3 grid((unsigned)chunks, (unsigned)((F_in + 64 * bm - 1) / (64 * bm)),
+                        (unsigned)((F_out + 64 * bn - 1) / (64 * bn)));
+        float* part = static_cast<float*>(workspace);
+#define EPP_LAUNCH_WG(BM, BN)                                                                                    \
+    do {                                                                                                         \
+        if (vec)                                                                                                 \
+            hipLaunchKernelGGL((k_weight_gradient<BM, BN, true>), grid, dim3(kBlock), 0, s, ids, n_rows, per, Y, \
+                               F_in, grad_X, F_out, part);                                                       \
+        else                                                                                                     \
+            hipLaunchKernelGGL((k_weight_gradient<BM, BN, false>), grid, dim3(kBlock), 0, s, ids, n_rows, per, Y, \
+                               F_in, grad_X, F_out, part);                                                       \
+    } while (0)
+        const bool vec = aligned4(F_in, F_out, Y, grad_X);
+        if (bm == 2 && bn == 2) EPP_LAUNCH_WG(2, 2);
+        else if (bm == 2) EPP_LAUNCH_WG(2, 1);
+        else if (bn == 2) EPP_LAUNCH_WG(1, 2);
+        else EPP_LAUNCH_WG(1, 1);
+#undef EPP_LAUNCH_WG
     }
     const int64_t total = (int64_t)F_in * F_out;
-    hipLaunchKernelGGL(k_weight_gradient_reduce, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
+    hipLaunchKernelGGL(k_weight_gradient_reduce, dim3((unsigned)((total + 15) / 16)), dim3(kBlock), 0, s,
                        static_cast<const float*>(workspace), chunks, total, grad_W);
     EPP_HIP_TRY(hipGetLastError());
     return EPP_OK;
@@ -203,8 +324,16 @@ extern "C" int epp_input_gradient(epp_paths_t* paths, int k, const float* grad_X
     int64_t n_rows = 0;
     EPP_TRY(row_set(paths, k, s, &ids, &n_rows));
     if (n_rows == 0) return EPP_OK;
-    const dim3 grid((unsigned)((n_rows + kTile - 1) / kTile), (unsigned)((F_in + kTile - 1) / kTile));
-    hipLaunchKernelGGL(k_input_gradient, grid, dim3(kBlock), 0, s, ids, n_rows, grad_X, F_out, W, F_in, grad_Y);
+    // rows are the long dimension: 128 of them per tile; 128 columns where F_in has them
+    const int bn = blocks_for(F_in);
+    const dim3 grid((unsigned)((n_rows + 127) / 128), (unsigned)((F_in + 64 * bn - 1) / (64 * bn)));
+    const bool vec = aligned4(F_out, F_out, grad_X, W);  // both operands are read along F_out
+#define EPP_LAUNCH_IG(BN, VEC)                                                                                  \
+    hipLaunchKernelGGL((k_input_gradient<BN, VEC>), grid, dim3(kBlock), 0, s, ids, n_rows, grad_X, F_out, W, F_in, \
+                       grad_Y)
+    if (bn == 2) { if (vec) EPP_LAUNCH_IG(2, true); else EPP_LAUNCH_IG(2, false); }
+    else { if (vec) EPP_LAUNCH_IG(1, true); else EPP_LAUNCH_IG(1, false); }
+#undef EPP_LAUNCH_IG
     EPP_HIP_TRY(hipGetLastError());
     return EPP_OK;
 }

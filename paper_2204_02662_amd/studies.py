@@ -2,6 +2,7 @@
 
     python -m paper_2204_02662_amd.studies gs    --config 4          # group-size sweep per layer (Sec. 5, Fig. 4 analogue)
     python -m paper_2204_02662_amd.studies depth --config 4 --F 64   # L = 2..6 (multi-layer study, Fig. 10 analogue)
+    python -m paper_2204_02662_amd.studies combine --config 5        # combination stage on active rows vs all rows
 
 Both print one JSON object per measurement.  Synthetic inputs only (graphgen).
 """
@@ -119,9 +120,58 @@ def depth_study(args):
         del paths
 
 
+def combine_study(args):
+    """Combination lines of Alg. 1's backward loop for every layer of a configuration: restricted
+    to N^{L-l-1} (this library), over all rows (this library, k = -1) and over all rows with the
+    vendor GEMM (torch.matmul).  Widths: W(l) is F_l x F_{l+1}, with F_L set to F_{L-1}."""
+    import torch
+
+    import graphgen
+    import paper_2204_02662_amd as epp
+
+    dev = torch.device("cuda", 0)
+    cfg = graphgen.make_config(args.config)
+    g, L = cfg.graph, cfg.L
+    rowptr, col, val = (torch.from_numpy(a).to(dev) for a in (g.rowptr, g.col, g.val))
+    paths = epp.epp_prepare(g.n, rowptr, col, val, torch.from_numpy(cfg.train_ids).to(dev), L)
+    widths = list(cfg.widths) + [cfg.widths[L - 1]]
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(cfg.seed(30))
+    for l in range(L - 1, -1, -1):
+        k = L - l - 1
+        Fi, Fo = widths[l], widths[l + 1]
+        rows = paths.active_set(k).long()
+        Y = torch.randn(g.n, Fi, generator=gen, device=dev)
+        W = torch.randn(Fi, Fo, generator=gen, device=dev)
+        G = torch.zeros(g.n, Fo, device=dev)
+        G[rows] = torch.randn(rows.numel(), Fo, generator=gen, device=dev)
+        Wg, Yg = torch.empty(Fi, Fo, device=dev), torch.zeros(g.n, Fi, device=dev)
+        ws = torch.empty(max(epp.epp_weight_gradient_workspace(paths, k, Fi, Fo),
+                             epp.epp_weight_gradient_workspace(paths, -1, Fi, Fo)), dtype=torch.uint8, device=dev)
+        R = rows.numel()
+        rec = {"study": "combine", "workload": cfg.name, "l": l, "k": k, "F_in": Fi, "F_out": Fo, "n": g.n,
+               "active_rows": R}
+        for name, kk in (("active", k), ("all_rows", -1)):
+            rec[f"weight_grad_{name}_ms"] = _time_ms(lambda: epp.epp_weight_gradient(paths, kk, Y, G, Wg, ws))
+            rec[f"input_grad_{name}_ms"] = _time_ms(lambda: epp.epp_input_gradient(paths, kk, G, W, Yg))
+        rec["weight_grad_vendor_gemm_ms"] = _time_ms(lambda: torch.matmul(Y.t(), G, out=Wg))
+        rec["input_grad_vendor_gemm_ms"] = _time_ms(lambda: torch.matmul(G, W.t(), out=Yg))
+        # algorithmic bytes (each operand row once) and flops of the restricted products
+        by = 4.0 * R * (Fi + Fo) + 4.0 * Fi * Fo
+        fl = 2.0 * R * Fi * Fo
+        for op in ("weight_grad", "input_grad"):
+            ms = rec[f"{op}_active_ms"]
+            rec[f"{op}_active_GBs"] = by / ms / 1e6
+            rec[f"{op}_active_TFLOPs"] = fl / ms / 1e9
+            rec[f"{op}_active_hbm_frac"] = by / ms / 1e6 / 8000.0
+            rec[f"{op}_active_mfma_frac"] = fl / ms / 1e9 / 157.3
+        print(json.dumps(rec), flush=True)
+        del Y, W, G, Wg, Yg, ws
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("study", choices=["gs", "depth"])
+    ap.add_argument("study", choices=["gs", "depth", "combine"])
     ap.add_argument("--config", type=int, default=4)
     ap.add_argument("--F", type=int, default=64)
     ap.add_argument("--Ls", type=str, default="2,3,4,5,6")
@@ -130,7 +180,7 @@ def main():
 
     assert torch.cuda.is_available(), "the studies need a GPU"
     torch.cuda.set_device(0)
-    (gs_study if args.study == "gs" else depth_study)(args)
+    {"gs": gs_study, "depth": depth_study, "combine": combine_study}[args.study](args)
 
 
 if __name__ == "__main__":
