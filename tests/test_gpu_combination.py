@@ -135,3 +135,48 @@ def test_backward_chain_matches_the_dense_model():
         # the inputs of the two chains differ by rounding only; compare loosely here, the tight
         # per-operation checks are above
         assert np.allclose(G, G_o, rtol=1e-4, atol=1e-5)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("cfg_id", [4, 5])
+def test_combination_at_benchmark_sizes(cfg_id):
+    """Full-size configurations, widths as the combine study times them (F_L = F_{L-1}).
+    W' is a reduction over millions of rows: the oracle computes a sampled 6 x 5 block of it
+    (all rows, fp64); Y' is checked on every 997th active row, every column."""
+    cfg = graphgen.make_config(cfg_id)
+    g, L = cfg.graph, cfg.L
+    print(f"[cfg {cfg_id}] oracle sets", flush=True)
+    sets_o = oracle.active_sets(g.n, g.rowptr, g.col, cfg.train_ids, L)
+    paths = gpu_prepare(g, cfg.train_ids, L)
+    widths = list(cfg.widths) + [cfg.widths[L - 1]]
+    d = dev()
+    for l in range(L - 1, -1, -1):
+        k = L - l - 1
+        Fi, Fo = widths[l], widths[l + 1]
+        member = sets_o[k]
+        print(f"[cfg {cfg_id}] layer {l}: {Fi} x {Fo}, {int(member.sum())} active rows", flush=True)
+        gen = torch.Generator(device=d)
+        gen.manual_seed(cfg.seed(40 + l))
+        Y = torch.randn(g.n, Fi, generator=gen, device=d)
+        W = torch.randn(Fi, Fo, generator=gen, device=d)
+        G = torch.randn(g.n, Fo, generator=gen, device=d)
+        G[torch.from_numpy(member == 0).to(d)] = float("nan")  # never read outside N^k
+        Wg = torch.empty(Fi, Fo, device=d)
+        Yg = torch.full((g.n, Fi), 3.0, device=d)
+        ws = torch.empty(epp.epp_weight_gradient_workspace(paths, k, Fi, Fo), dtype=torch.uint8, device=d)
+        epp.epp_weight_gradient(paths, k, Y, G, Wg, ws)
+        epp.epp_input_gradient(paths, k, G, W, Yg)
+        torch.cuda.synchronize()
+        Yh, Gh = Y.cpu().numpy(), np.nan_to_num(G.cpu().numpy())
+        I = np.unique(np.linspace(0, Fi - 1, 6).astype(int))
+        J = np.unique(np.linspace(0, Fo - 1, 5).astype(int))
+        want_w, scale_w = oracle.weight_gradient(Yh[:, I], Gh[:, J], member)
+        _close(Wg.cpu().numpy()[np.ix_(I, J)], want_w, scale_w, f"cfg {cfg_id} W' l={l}")
+        rows = np.flatnonzero(member)[::997]
+        sample = np.zeros(g.n, np.uint8)
+        sample[rows] = 1
+        want_y, scale_y = oracle.input_gradient(Gh, W.cpu().numpy(), sample)
+        got_y = Yg.cpu().numpy()
+        _close(got_y[rows], want_y[rows], scale_y[rows], f"cfg {cfg_id} Y' l={l}")
+        assert np.all(got_y[member == 0] == 3.0)
+        del Y, W, G, Wg, Yg, ws, Yh, Gh, got_y, want_y, scale_y
