@@ -108,6 +108,7 @@ def main():
     ap.add_argument("--config", type=int, default=int(os.environ.get("EPP_BENCH_CONFIG", "5")))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-all-active", action="store_true")
+    ap.add_argument("--no-combination", action="store_true", help="skip the combination-stage report")
     ap.add_argument("--cpu-budget-s", type=float, default=15.0)
     ap.add_argument("--layers", type=str, default="", help="comma list of layers to run (profiling); default all")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -263,6 +264,51 @@ def main():
         result["if_else"] = {"ms_per_epoch": ms_ie, "steps": k_full,
                              "layers": [{"l": l, "F": cfg.widths[l], "ms": ie_layer_ms[l]} for l in order]}
         result["speedup_partial_over_if_else"] = ms_ie / ms_partial if ms_partial > 0 else None
+
+    # combination stage of the backward loop on the active rows (reported beside the metric, never
+    # part of it): W'(l) = Y(l)^T X'(l+1), Y'(l) = X'(l+1) W(l)^T with W(l) of F_l x F_{l+1}, F_L = F_{L-1}
+    if not args.no_combination and not args.layers:
+        widths = list(cfg.widths) + [cfg.widths[L - 1]]
+        comb = []
+        for l in order:
+            k, Fi, Fo = L - l - 1, widths[l], widths[l + 1]
+            rows = paths.active_set(k).long()
+            gen.manual_seed(cfg.seed(30 + l))
+            Y = torch.randn(g.n, Fi, generator=gen, device=dev)
+            W = torch.randn(Fi, Fo, generator=gen, device=dev)
+            G = torch.zeros(g.n, Fo, device=dev)
+            G[rows] = torch.randn(rows.numel(), Fo, generator=gen, device=dev)
+            Wg = torch.empty(Fi, Fo, device=dev)
+            ws = torch.empty(epp.epp_weight_gradient_workspace(paths, k, Fi, Fo), dtype=torch.uint8, device=dev)
+
+            def ev_ms(fn, reps=5):
+                fn()
+                torch.cuda.synchronize()
+                e = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+                for a, b in e:
+                    a.record()
+                    fn()
+                    b.record()
+                torch.cuda.synchronize()
+                return float(np.median([a.elapsed_time(b) for a, b in e]))
+
+            R = rows.numel()
+            w_ms = ev_ms(lambda: epp.epp_weight_gradient(paths, k, Y, G, Wg, ws))
+            y_ms = ev_ms(lambda: epp.epp_input_gradient(paths, k, G, W, grad_out[l]))
+            wv_ms = ev_ms(lambda: torch.matmul(Y.t(), G, out=Wg))
+            yv_ms = ev_ms(lambda: torch.matmul(G, W.t(), out=grad_out[l]))
+            grad_out[l].zero_()
+            by, fl_ = 4.0 * R * (Fi + Fo) + 4.0 * Fi * Fo, 2.0 * R * Fi * Fo
+            comb.append({"l": l, "k": k, "F_in": Fi, "F_out": Fo, "active_rows": R,
+                         "weight_gradient_ms": w_ms, "input_gradient_ms": y_ms,
+                         "vendor_gemm_all_rows_ms": {"weight_gradient": wv_ms, "input_gradient": yv_ms},
+                         "algorithmic_bytes": by, "flops": fl_,
+                         "weight_gradient_hbm_frac": by / w_ms / 1e6 / HBM_PEAK_GBS,
+                         "weight_gradient_mfma_f32_frac": fl_ / w_ms / 1e9 / 157.3,
+                         "input_gradient_hbm_frac": by / y_ms / 1e6 / HBM_PEAK_GBS,
+                         "input_gradient_mfma_f32_frac": fl_ / y_ms / 1e9 / 157.3})
+            del Y, W, G, Wg, ws
+        result["combination_active_rows"] = {"dtype": "f32", "layers": comb}
 
     # launch-bound workloads: the same epoch captured once in a HIP graph and replayed
     if ms_partial < 1.0 and not args.layers:
