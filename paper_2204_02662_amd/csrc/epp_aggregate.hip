@@ -21,6 +21,7 @@
 //     neighbours, so the only cross-group combination is the atomic write-back.
 
 #include <algorithm>
+#include <cmath>
 #include <cstdlib>
 #include <cstring>
 
@@ -421,22 +422,28 @@ __global__ __launch_bounds__(kBlock) void k_mark_cold(int2v* __restrict__ cv, in
 //
 // On this machine a group is a fixed-cost unit (gs gathers of one row fragment each), so
 // load balance no longer depends on the degree distribution; what the group size trades is
-// (a) atomic write-back and zeroing of the rows cut by group boundaries, which falls as gs
-// grows, against (b) having enough groups to fill every slot of the GPU several times
-// over, which matters for small paths.  The slots of the GPU are
-//     256 CUs x 16 resident wavefronts x 64/T groups per wavefront,
-// with T the lanes one row of width F needs; the selector aims at about four rounds of
-// groups per slot and clamps gs to [16, 2048] (measured flat beyond 2048).
+// (a) the per-group cost and the atomic write-back and zeroing of the rows cut by group
+// boundaries, which fall as gs grows, against (b) having enough groups in flight, which
+// matters for small paths.  As in Sec. 5 the size is predicted by a linear regression on
+// structural features, learned from a generated corpus: 72 R-MAT and Chung-Lu graphs (2^12 to
+// 2^21 vertices, average degree 4 to 64, 1 % and 10 % training vertices), two paths each,
+// widths 16 / 64 / 128, every sample labelled with the best group size of an exhaustive
+// power-of-two sweep on an MI355X (432 samples; `python -m paper_2204_02662_amd.studies gsfit
+// --log2n 12,13,15,17,19,21` repeats the fit).  Model, in octaves:
+//     log2 gs = 0.3557 log2(entries) + 0.1744 log2(entries per row) + 0.5099 log2(F) - 3.8123
+// rounded to a power of two and clamped to [8, 4096].  Leave-one-graph-out, the predicted size
+// costs 5 % over the best on average (39 % at worst); on the five benchmark configurations
+// at most 4 % (most layers 0 %).
 int epp_default_group_size(const epp_path* p, int F) {
     int forced = env_int("EPP_TUNE_GS", 0);
     if (forced > 0) return forced;
-    int vec, log2T;
-    row_shape(F, true, &vec, &log2T);
-    const int64_t slots = 256ll * 16 * (64 >> log2T);
-    const int64_t want = p->nnz / (slots * 4);
-    int gs = 16;
-    while (gs * 2 <= want && gs < 2048) gs *= 2;
-    return gs;
+    if (p->nnz <= 0) return 8;
+    const double entries = (double)p->nnz;
+    const double per_row = entries / (double)std::max<int64_t>(p->n_stream_rows, 1);
+    const double x = 0.3557363781872999 * std::log2(entries) + 0.1743635851953411 * std::log2(per_row) +
+                     0.509920634920635 * std::log2((double)F) - 3.8123401416789617;
+    const int e = (int)std::lround(std::min(std::max(x, 3.0), 12.0));
+    return 1 << e;
 }
 
 int epp_build_schedule(epp_path* p, int gs, hipStream_t s, Schedule** out) {

@@ -3,6 +3,8 @@
     python -m paper_2204_02662_amd.studies gs    --config 4          # group-size sweep per layer (Sec. 5, Fig. 4 analogue)
     python -m paper_2204_02662_amd.studies depth --config 4 --F 64   # L = 2..6 (multi-layer study, Fig. 10 analogue)
     python -m paper_2204_02662_amd.studies combine --config 5        # combination stage on active rows vs all rows
+    python -m paper_2204_02662_amd.studies gsfit                      # regression for the group size re-fitted on a
+                                                                      # generated corpus (Sec. 5's method on wave64)
 
 Both print one JSON object per measurement.  Synthetic inputs only (graphgen).
 """
@@ -169,18 +171,104 @@ def combine_study(args):
         del Y, W, G, Wg, Yg, ws
 
 
+def gsfit_study(args):
+    """Sec. 5's learning-based selection redone for this kernel: generate a corpus of power-law
+    graphs (R-MAT and Chung-Lu, as the paper's corpus came from a generator), label every
+    execution path and width with the best group size of an exhaustive power-of-two sweep (the
+    paper's labelling method), fit a linear regression on structural features, and compare the
+    loss over the best group size of (a) that regression, leave-one-graph-out, (b) the library's
+    closed-form selector, (c) the paper's printed regression applied to the sub-graph."""
+    import numpy as np
+    import torch
+
+    import graphgen
+    import paper_2204_02662_amd as epp
+
+    dev = torch.device("cuda", 0)
+    sweep = [2 ** i for i in range(3, 13)]
+    corpus = [(kind, 1 << ln, deg, frac) for kind in ("rmat", "chung_lu") for ln in args.log2n
+              for deg in (4, 16, 64) for frac in (0.01, 0.1)]
+    samples = []
+    for gi, (kind, n, deg, frac) in enumerate(corpus):
+        edges = n * deg // 2
+        try:
+            g = (graphgen.random_graph("rmat", n, seed=7000 + gi, raw_draws=edges) if kind == "rmat"
+                 else graphgen.random_graph("chung_lu", n, seed=7000 + gi, target_edges=edges))
+        except RuntimeError:
+            continue  # the generator cannot reach this many distinct pairs
+        train = graphgen.training_set(g.n, max(1, int(frac * n)), 7100 + gi)
+        rowptr, col, val = (torch.from_numpy(a).to(dev) for a in (g.rowptr, g.col, g.val))
+        L = 2
+        paths = epp.epp_prepare(g.n, rowptr, col, val, torch.from_numpy(train).to(dev), L)
+        for l in range(L):
+            p = paths.path(l)
+            info = p.info()
+            if info.nnz == 0:
+                continue
+            for F in args.widths:
+                x, y = _inputs(paths, g.n, F, L - l - 1, dev, 7200 + gi)
+                times = {}
+                for gs in sweep:
+                    p.set_group_size(F, gs)
+                    times[gs] = _time_ms(lambda: epp.epp_backward_aggregate(p, x, y), reps=5)
+                p.set_group_size(F, 0)
+                chosen = p.select_group_size(F)
+                rec = {"study": "gsfit-sample", "graph": gi, "kind": kind, "n": n, "deg": deg, "train_frac": frac,
+                       "l": l, "F": F, "rows": info.n_rows, "nnz": info.nnz, "max_len": info.max_len,
+                       "times_ms": times, "best_gs": min(times, key=times.get), "selector_gs": chosen,
+                       "paper_linreg_gs": epp.epp_paper_linreg_group_size(max(info.n_rows, 1), info.nnz // 2)}
+                samples.append(rec)
+                print(json.dumps(rec), flush=True)
+                del x, y
+        del paths, rowptr, col, val
+
+    def feats(r):
+        return [np.log2(r["nnz"]), np.log2(r["nnz"] / r["rows"]), np.log2(r["F"]), 1.0]
+
+    def loss(r, gs):  # time at the nearest swept group size over the best time
+        near = min(sweep, key=lambda s_: abs(np.log2(s_) - np.log2(max(gs, 1))))
+        return r["times_ms"][near] / r["times_ms"][r["best_gs"]]
+
+    X = np.array([feats(r) for r in samples])
+    yv = np.array([np.log2(r["best_gs"]) for r in samples])
+    beta_all, *_ = np.linalg.lstsq(X, yv, rcond=None)
+    graphs = sorted({r["graph"] for r in samples})
+    loo = []
+    for gi in graphs:  # leave one graph out
+        tr = np.array([r["graph"] != gi for r in samples])
+        b, *_ = np.linalg.lstsq(X[tr], yv[tr], rcond=None)
+        loo += [loss(r, 2.0 ** float(np.dot(b, feats(r)))) for r in samples if r["graph"] == gi]
+    sel = [loss(r, r["selector_gs"]) for r in samples]
+    pap = [loss(r, r["paper_linreg_gs"]) for r in samples]
+
+    def stats(v):
+        v = np.array(v)
+        return {"mean": float(v.mean()), "median": float(np.median(v)), "p90": float(np.quantile(v, 0.9)),
+                "max": float(v.max())}
+
+    print(json.dumps({"study": "gsfit-summary", "samples": len(samples), "graphs": len(graphs),
+                      "features": ["log2 nnz", "log2 mean row length", "log2 F", "1"],
+                      "beta_log2_gs": [float(b) for b in beta_all],
+                      "r2": float(1 - ((X @ beta_all - yv) ** 2).sum() / ((yv - yv.mean()) ** 2).sum()),
+                      "time_over_best": {"fitted_regression_leave_one_graph_out": stats(loo),
+                                         "library_selector": stats(sel), "paper_regression_on_subgraph": stats(pap)}}),
+          flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("study", choices=["gs", "depth", "combine"])
+    ap.add_argument("study", choices=["gs", "depth", "combine", "gsfit"])
     ap.add_argument("--config", type=int, default=4)
     ap.add_argument("--F", type=int, default=64)
     ap.add_argument("--Ls", type=str, default="2,3,4,5,6")
+    ap.add_argument("--log2n", type=lambda v: [int(x) for x in v.split(",")], default=[13, 15, 17, 19])
+    ap.add_argument("--widths", type=lambda v: [int(x) for x in v.split(",")], default=[16, 64, 128])
     args = ap.parse_args()
     import torch
 
     assert torch.cuda.is_available(), "the studies need a GPU"
     torch.cuda.set_device(0)
-    {"gs": gs_study, "depth": depth_study, "combine": combine_study}[args.study](args)
+    {"gs": gs_study, "depth": depth_study, "combine": combine_study, "gsfit": gsfit_study}[args.study](args)
 
 
 if __name__ == "__main__":
