@@ -180,3 +180,60 @@ def test_combination_at_benchmark_sizes(cfg_id):
         _close(got_y[rows], want_y[rows], scale_y[rows], f"cfg {cfg_id} Y' l={l}")
         assert np.all(got_y[member == 0] == 3.0)
         del Y, W, G, Wg, Yg, ws, Yh, Gh, got_y, want_y, scale_y
+
+
+def test_backward_epoch_in_a_hip_graph():
+    """Combination and aggregation of every layer, chained as in Alg. 1's backward loop, captured
+    once in a HIP graph (after a first eager epoch that builds schedules and the id list of N^0)
+    and replayed with eager work in between: every replay must equal the eager epoch bit for bit
+    on the weight gradients (fixed summation order) and within tolerance of the oracle chain."""
+    g = graphgen.random_graph("chung_lu", 6000, seed=460, target_edges=30_000)
+    train = graphgen.training_set(g.n, 60, 461)
+    L, widths = 2, [24, 16, 8]
+    sets_o, _ = oracle.prepare(g.n, g.rowptr, g.col, g.val, train, L)
+    paths = gpu_prepare(g, train, L)
+    d = dev()
+    Ys = [torch.from_numpy(_rand((g.n, widths[l]), 462 + l)).to(d) for l in range(L)]
+    Ws = [torch.from_numpy(_rand((widths[l], widths[l + 1]), 465 + l) / 4).to(d) for l in range(L)]
+    G_top = np.zeros((g.n, widths[L]), np.float32)
+    G_top[sets_o[0] == 1] = _rand((int(sets_o[0].sum()), widths[L]), 468)
+    Gs = [torch.zeros(g.n, widths[l], device=d) for l in range(L)] + [torch.from_numpy(G_top).to(d)]
+    Ygs = [torch.zeros(g.n, widths[l], device=d) for l in range(L)]
+    Wgs = [torch.empty(widths[l], widths[l + 1], device=d) for l in range(L)]
+    wss = [torch.empty(epp.epp_weight_gradient_workspace(paths, L - l - 1, widths[l], widths[l + 1]),
+                       dtype=torch.uint8, device=d) for l in range(L)]
+    ps = [paths.path(l) for l in range(L)]
+
+    def epoch():
+        for l in range(L - 1, -1, -1):
+            k = L - l - 1
+            epp.epp_weight_gradient(paths, k, Ys[l], Gs[l + 1], Wgs[l], wss[l])
+            epp.epp_input_gradient(paths, k, Gs[l + 1], Ws[l], Ygs[l])
+            epp.epp_backward_aggregate(ps[l], Ygs[l], Gs[l])
+
+    epoch()
+    torch.cuda.synchronize()
+    eager_w = [w.clone() for w in Wgs]
+    eager_g0 = Gs[0].clone()
+    # oracle chain on all vertices
+    Go = G_top
+    for l in range(L - 1, -1, -1):
+        want_w, scale_w = oracle.weight_gradient(Ys[l].cpu().numpy(), Go)
+        _close(eager_w[l].cpu().numpy(), want_w, scale_w, f"eager W' l={l}")
+        yg, _ = oracle.input_gradient(Go, Ws[l].cpu().numpy())
+        Go = oracle.full_aggregate(g.n, g.rowptr, g.col, g.val, yg)
+    assert np.allclose(eager_g0.cpu().numpy(), Go, rtol=1e-4, atol=1e-5)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        epoch()
+    for rep in range(3):
+        for w in Wgs:
+            w.fill_(float(rep + 1))          # eager work between replays
+        for ws in wss:
+            ws.fill_(255)                    # stale partial sums must not leak
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for l in range(L):
+            assert torch.equal(Wgs[l], eager_w[l]), f"replay {rep} W' l={l}"
+        assert torch.allclose(Gs[0], eager_g0, rtol=1e-6, atol=1e-7)  # atomics on cut rows may reorder sums
