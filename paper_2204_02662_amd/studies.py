@@ -3,6 +3,7 @@
     python -m paper_2204_02662_amd.studies gs    --config 4          # group-size sweep per layer (Sec. 5, Fig. 4 analogue)
     python -m paper_2204_02662_amd.studies depth --config 4 --F 64   # L = 2..6 (multi-layer study, Fig. 10 analogue)
     python -m paper_2204_02662_amd.studies combine --config 5        # combination stage on active rows vs all rows
+    python -m paper_2204_02662_amd.studies overlap --config 5        # path preparing hidden behind the forward pass
     python -m paper_2204_02662_amd.studies gsfit                      # regression for the group size re-fitted on a
                                                                       # generated corpus (Sec. 5's method on wave64)
 
@@ -171,6 +172,58 @@ def combine_study(args):
         del Y, W, G, Wg, Yg, ws
 
 
+def overlap_study(args):
+    """On-the-fly preparation (the paper's last experiment): epp_prepare on a second stream while
+    the first forward pass (all-active aggregations of every layer, this build's own kernel) runs
+    on the main stream.  Reports both alone, back to back, and overlapped."""
+    import time
+
+    import torch
+
+    import graphgen
+    import paper_2204_02662_amd as epp
+
+    dev = torch.device("cuda", 0)
+    cfg = graphgen.make_config(args.config)
+    g, L = cfg.graph, cfg.L
+    rowptr, col, val = (torch.from_numpy(a).to(dev) for a in (g.rowptr, g.col, g.val))
+    train = torch.from_numpy(cfg.train_ids).to(dev)
+    full = epp.epp_prepare_full(g.n, rowptr, col, val)
+    xs = [torch.randn(g.n, cfg.widths[l], device=dev) for l in range(L)]
+    ys = [torch.empty_like(x) for x in xs]
+
+    def forward():
+        for l in range(L):
+            epp.epp_full_aggregate(full, xs[l], ys[l])
+
+    def wall(fn, reps=5):
+        out = []
+        for _ in range(reps):
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            out.append((time.perf_counter() - t) * 1e3)
+        return sorted(out)[len(out) // 2]
+
+    forward()  # schedules of the all-active graph
+    side = torch.cuda.Stream()
+
+    def prepare_only():
+        epp.epp_prepare(g.n, rowptr, col, val, train, L)
+
+    def overlapped():
+        forward()                      # enqueued on the main stream, returns at once
+        with torch.cuda.stream(side):  # prepare runs (and waits) on its own stream
+            epp.epp_prepare(g.n, rowptr, col, val, train, L)
+
+    f_ms, p_ms = wall(forward), wall(prepare_only)
+    both_ms = wall(overlapped)
+    print(json.dumps({"study": "overlap", "workload": cfg.name, "forward_all_active_ms": f_ms, "prepare_ms": p_ms,
+                      "back_to_back_ms": f_ms + p_ms, "overlapped_ms": both_ms,
+                      "prepare_cost_hidden": 1.0 - max(both_ms - f_ms, 0.0) / p_ms}), flush=True)
+
+
 def gsfit_study(args):
     """Sec. 5's learning-based selection redone for this kernel: generate a corpus of power-law
     graphs (R-MAT and Chung-Lu, as the paper's corpus came from a generator), label every
@@ -257,7 +310,7 @@ def gsfit_study(args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("study", choices=["gs", "depth", "combine", "gsfit"])
+    ap.add_argument("study", choices=["gs", "depth", "combine", "gsfit", "overlap"])
     ap.add_argument("--config", type=int, default=4)
     ap.add_argument("--F", type=int, default=64)
     ap.add_argument("--Ls", type=str, default="2,3,4,5,6")
@@ -268,7 +321,8 @@ def main():
 
     assert torch.cuda.is_available(), "the studies need a GPU"
     torch.cuda.set_device(0)
-    {"gs": gs_study, "depth": depth_study, "combine": combine_study, "gsfit": gsfit_study}[args.study](args)
+    {"gs": gs_study, "depth": depth_study, "combine": combine_study, "gsfit": gsfit_study,
+     "overlap": overlap_study}[args.study](args)
 
 
 if __name__ == "__main__":
