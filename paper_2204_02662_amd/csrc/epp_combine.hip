@@ -67,25 +67,24 @@ __global__ __launch_bounds__(kBlock) void k_input_gradient(const int32_t* __rest
     }
     __syncthreads();
     const int tr = t >> 3, k = 4 * (t & 7);
-    const float* pa[NA];
-    const float* pb[NB];
+    int64_t oa[NA], ob[NB];  // element offset of this thread's piece at k0 = 0; -1: no such row
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
         const int64_t id = sid[tr + 32 * i];
-        pa[i] = id >= 0 ? G + id * Fo + k : nullptr;
+        oa[i] = id >= 0 ? id * Fo + k : -1;
     }
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
         const int n = n0 + tr + 32 * i;
-        pb[i] = n < Fi ? W + (int64_t)n * Fo + k : nullptr;
+        ob[i] = n < Fi ? (int64_t)n * Fo + k : -1;
     }
     float4v ra[NA], rb[NB];
     auto fetch = [&](int k0) {
         const int valid = Fo - (k0 + k);
 #pragma unroll
-        for (int i = 0; i < NA; ++i) ra[i] = load4<VEC>(pa[i] + k0, pa[i] ? valid : 0);
+        for (int i = 0; i < NA; ++i) ra[i] = load4<VEC>(G + (oa[i] >= 0 ? oa[i] + k0 : 0), oa[i] >= 0 ? valid : 0);
 #pragma unroll
-        for (int i = 0; i < NB; ++i) rb[i] = load4<VEC>(pb[i] + k0, pb[i] ? valid : 0);
+        for (int i = 0; i < NB; ++i) rb[i] = load4<VEC>(W + (ob[i] >= 0 ? ob[i] + k0 : 0), ob[i] >= 0 ? valid : 0);
     };
     floatx16 acc[BM][BN] = {};
     fetch(0);
@@ -150,8 +149,8 @@ __global__ __launch_bounds__(kBlock) void k_weight_gradient(const int32_t* __res
     auto vertex = [&](int64_t r) -> int64_t { return r < last ? (ids ? (int64_t)ids[r] : r) : -1; };
     float4v ra[NA], rb[NB];
     auto fetch = [&](int64_t id) {
-        const float* y = Y + id * Fi + m0 + c4;
-        const float* g = G + id * Fo + n0 + c4;
+        const float* y = Y + (id >= 0 ? id * Fi + m0 + c4 : 0);
+        const float* g = G + (id >= 0 ? id * Fo + n0 + c4 : 0);
 #pragma unroll
         for (int i = 0; i < NA; ++i) ra[i] = load4<VEC>(y + 32 * i, id >= 0 ? Fi - (m0 + c4 + 32 * i) : 0);
 #pragma unroll

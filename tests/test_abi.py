@@ -45,6 +45,10 @@ def test_host_side_argument_checks_need_no_gpu():
         csr = epp._Csr(n, nnz, dummy, dummy, dummy)
         assert lib.epp_prepare(ctypes.byref(csr), None, 0, 2, None, ctypes.byref(out)) == want
         assert lib.epp_prepare_full(ctypes.byref(csr), None, ctypes.byref(out)) == want
+    # combination stage: NULL handles and NULL matrices are refused on the host
+    assert lib.epp_weight_gradient_workspace(None, 0, 16, 16) == epp.EPP_ERR_INVALID_ARG
+    assert lib.epp_weight_gradient(None, 0, dummy, 16, dummy, 16, dummy, dummy, 1 << 20, None) == epp.EPP_ERR_INVALID_ARG
+    assert lib.epp_input_gradient(None, 0, dummy, 16, dummy, 16, dummy, None) == epp.EPP_ERR_INVALID_ARG
     csr = epp._Csr(10, 10, dummy, dummy, dummy)
     assert lib.epp_prepare(ctypes.byref(csr), None, 0, 0, None, ctypes.byref(out)) == epp.EPP_ERR_INVALID_ARG  # L < 1
     assert lib.epp_prepare(ctypes.byref(csr), None, 5, 1, None, ctypes.byref(out)) == epp.EPP_ERR_INVALID_ARG  # ids NULL
