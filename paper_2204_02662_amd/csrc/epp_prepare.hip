@@ -227,7 +227,8 @@ __global__ __launch_bounds__(kBlock) void k_bitmap_compact(const unsigned long l
 
 __device__ __forceinline__ int length_class(int len) { return len <= 1 ? 0 : 32 - __clz(len - 1); }
 
-// Row-length histogram by class and the maximal length.
+// Row-length histogram by class and the maximal length.  Grid-stride; a wavefront adds one
+// count per distinct class among its 64 rows (ballots), a workgroup 33 global atomics in all.
 __global__ __launch_bounds__(kBlock) void k_len_hist(const int32_t* __restrict__ rowptr, int64_t n_rows,
                                                      unsigned long long* __restrict__ hist, int* __restrict__ max_len) {
     __shared__ int h[EPP_NCLASS];
@@ -235,12 +236,27 @@ __global__ __launch_bounds__(kBlock) void k_len_hist(const int32_t* __restrict__
     if (threadIdx.x < EPP_NCLASS) h[threadIdx.x] = 0;
     if (threadIdx.x == 0) mx = 0;
     __syncthreads();
-    int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (r < n_rows) {
-        int len = rowptr[r + 1] - rowptr[r];
-        atomicAdd(&h[length_class(len)], 1);
-        atomicMax(&mx, len);
+    const int lane = threadIdx.x & 63;
+    int my_max = 0;
+    const int64_t span = (int64_t)gridDim.x * kBlock;
+    // whole wavefronts enter every iteration, so the ballots below see all 64 lanes
+    for (int64_t base = (int64_t)blockIdx.x * kBlock + (threadIdx.x & ~63); base < n_rows; base += span) {
+        const int64_t r = base + lane;
+        int cls = -1;
+        if (r < n_rows) {
+            const int len = rowptr[r + 1] - rowptr[r];
+            my_max = max(my_max, len);
+            cls = length_class(len);
+        }
+        unsigned long long todo = __ballot(cls >= 0);
+        while (todo) {
+            const int c = __shfl(cls, __ffsll((long long)todo) - 1);
+            const unsigned long long same = __ballot(cls == c);
+            if (lane == __ffsll((long long)same) - 1) atomicAdd(&h[c], __popcll(same));
+            todo &= ~same;
+        }
     }
+    if (my_max) atomicMax(&mx, my_max);
     __syncthreads();
     if (threadIdx.x < EPP_NCLASS && h[threadIdx.x]) atomicAdd(&hist[threadIdx.x], (unsigned long long)h[threadIdx.x]);
     if (threadIdx.x == 0 && mx) atomicMax(max_len, mx);
@@ -366,7 +382,7 @@ int epp_path_finish(epp_path* p, hipStream_t s) {
     if (p->n_rows > 0) {
         // canonical rows: the all-active graph counts its empty rows too
         const int32_t* ptr = p->all_rows ? p->full_rowptr.as<int32_t>() : p->rowptr.as<int32_t>();
-        hipLaunchKernelGGL(k_len_hist, dim3(grid_for(p->n_rows, kBlock)), dim3(kBlock), 0, s, ptr,
+        hipLaunchKernelGGL(k_len_hist, dim3(std::min(grid_for(p->n_rows, kBlock), 2048u)), dim3(kBlock), 0, s, ptr,
                            p->n_rows, stats.as<unsigned long long>(),
                            reinterpret_cast<int*>(stats.as<unsigned long long>() + EPP_NCLASS));
         EPP_HIP_TRY(hipGetLastError());
@@ -382,9 +398,8 @@ int epp_path_finish(epp_path* p, hipStream_t s) {
         hipLaunchKernelGGL(k_mark_row_ends, dim3(grid_for(p->n_stream_rows, kBlock)), dim3(kBlock), 0, s,
                            p->rowptr.as<int32_t>(), p->n_stream_rows, p->cv.as<int2>());
         EPP_HIP_TRY(hipGetLastError());
-        EPP_HIP_TRY(hipStreamSynchronize(s));
     }
-    return EPP_OK;
+    return EPP_OK;  // the callers synchronise once, before they return the handle
 }
 
 extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t n_train, int L,
@@ -561,6 +576,7 @@ extern "C" int epp_prepare_full(const epp_csr_t* g, epp_stream_t stream, epp_pat
         }
     }
     EPP_TRY(epp_path_finish(p, s));
+    EPP_HIP_TRY(hipStreamSynchronize(s));
     guard.p = nullptr;
     *out = p;
     return EPP_OK;
