@@ -68,3 +68,20 @@ def test_paper_linear_regression_group_size():
     assert got == want == [2, 2, 2, 10, 12, 6, 9, 15]
     # far outside the fitted domain the value clamps to 1 (e.g. a path of configuration 4)
     assert epp.epp_paper_linreg_group_size(2_449_029, 61_900_000) == 1
+
+
+def test_header_is_plain_c_and_links_from_c(tmp_path):
+    """include/epp.h compiles as C99 and a C program linked against libepp.so runs the host-side
+    argument checks (no GPU involved)."""
+    import subprocess
+
+    import paper_2204_02662_amd as epp
+
+    epp.load_library()
+    exe = tmp_path / "abi_host_checks"
+    so_dir = epp.SO.parent
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-I", str(ROOT / "include"),
+                           str(ROOT / "tests" / "c" / "abi_host_checks.c"), "-o", str(exe),
+                           "-L", str(so_dir), "-lepp", f"-Wl,-rpath,{so_dir}"])
+    out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert out.returncode == 0 and out.stdout.strip().endswith("ok"), out.stdout + out.stderr
