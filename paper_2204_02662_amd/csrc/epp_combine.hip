@@ -5,10 +5,13 @@
 // list of N^k only: the rows are gathered (and, for Y', scattered) by vertex id, everything
 // else is a dense contraction and runs on the matrix cores in fp32 (v_mfma_f32_32x32x2_f32).
 //
-// Both kernels give a workgroup of four wavefronts (2 x 2) an output tile of 64 BM x 64 BN,
-// every wavefront BM x BN accumulator blocks of 32 x 32, and step through the contraction 32
-// at a time: the operand tiles of the next step are fetched into registers while the matrix
-// cores work on the current ones in LDS.
+// Both kernels give a workgroup of four wavefronts, arranged WM x WN, an output tile of
+// 32 WM BM x 32 WN BN, every wavefront BM x BN accumulator blocks of 32 x 32, and step through
+// the contraction 32 at a time: the operand tiles of the next step are fetched into registers
+// while the matrix cores work on the current ones in LDS.  The arrangement follows the matrix:
+// 2 x 2 wavefronts with up to 2 x 2 blocks each for wide outputs, 4 x 1 (a 128 x 32 tile) when
+// one side has at most 32 columns, as the weight matrices of a GCN with 16 hidden units or a
+// few classes do.
 //
 // Operand layout of the 32x32x2 instruction: lane l supplies A[l % 32][l / 32] and
 // B[l / 32][l % 32]; element j of its accumulator is C[8 (j / 4) + 4 (l / 32) + j % 4][l % 32].
@@ -46,19 +49,20 @@ __device__ __forceinline__ float4v load4(const float* __restrict__ p, int valid)
 // Thread mapping of all tile loads: eight threads per row, four consecutive floats each, so a
 // row segment of 32 floats is one 128-byte access and a thread needs one vertex id per row.
 
-// Y'[id, n] = sum_k X'[id, k] W[n, k] for the ids of one tile of 128 rows and 64 BN columns n.
-template <int BN, bool VEC>
+// Y'[id, n] = sum_k X'[id, k] W[n, k] for the ids of one tile of 32 WM BM rows and 32 WN BN columns n.
+template <int WM, int WN, int BM, int BN, bool VEC>
 __global__ __launch_bounds__(kBlock) void k_input_gradient(const int32_t* __restrict__ ids, int64_t n_rows,
                                                            const float* __restrict__ G, int Fo,
                                                            const float* __restrict__ W, int Fi,
                                                            float* __restrict__ Yg) {
-    constexpr int BM = 2, TM = 64 * BM, TN = 64 * BN;
+    static_assert(WM * WN == 4, "four wavefronts per workgroup");
+    constexpr int TM = 32 * WM * BM, TN = 32 * WN * BN;
     constexpr int NA = TM / 32, NB = TN / 32;  // rows per thread and step
     __shared__ float As[TM][kStep + 1];   // X' rows of the tile, [row][k]
     __shared__ float Bs[kStep][TN + 1];   // W^T, [k][n]
     __shared__ int64_t sid[TM];           // vertex of each tile row, -1 past the end
     const int t = threadIdx.x, lane = t & 63, w = t >> 6;
-    const int wm = w & 1, wn = w >> 1;
+    const int wm = w % WM, wn = w / WM;
     const int64_t row0 = (int64_t)blockIdx.x * TM;
     const int n0 = blockIdx.y * TN;
     for (int r = t; r < TM; r += kBlock) {
@@ -128,20 +132,21 @@ __global__ __launch_bounds__(kBlock) void k_input_gradient(const int32_t* __rest
         }
 }
 
-// partial[chunk][m][n] = sum over the chunk's rows of Y[id, m] X'[id, n], one tile of 64 BM x 64 BN.
+// partial[chunk][m][n] = sum over the chunk's rows of Y[id, m] X'[id, n], one tile of 32 WM BM x 32 WN BN.
 // The vertex id of a row is fetched one step before the row itself, so that the row loads of a
 // step never wait for an id.
-template <int BM, int BN, bool VEC>
+template <int WM, int WN, int BM, int BN, bool VEC>
 __global__ __launch_bounds__(kBlock) void k_weight_gradient(const int32_t* __restrict__ ids, int64_t n_rows,
                                                             int64_t rows_per_chunk, const float* __restrict__ Y,
                                                             int Fi, const float* __restrict__ G, int Fo,
                                                             float* __restrict__ partial) {
-    constexpr int TM = 64 * BM, TN = 64 * BN;
+    static_assert(WM * WN == 4, "four wavefronts per workgroup");
+    constexpr int TM = 32 * WM * BM, TN = 32 * WN * BN;
     constexpr int NA = TM / 32, NB = TN / 32;  // 4-float pieces per thread and step
     __shared__ __attribute__((aligned(16))) float As[kStep][TM];   // Y rows, [row][m]
     __shared__ __attribute__((aligned(16))) float Bs[kStep][TN];   // X' rows, [row][n]
     const int t = threadIdx.x, lane = t & 63, w = t >> 6;
-    const int wm = w & 1, wn = w >> 1;
+    const int wm = w % WM, wn = w / WM;
     const int m0 = blockIdx.y * TM, n0 = blockIdx.z * TN;
     const int64_t first = (int64_t)blockIdx.x * rows_per_chunk;
     const int64_t last = std::min<int64_t>(first + rows_per_chunk, n_rows);
@@ -226,8 +231,20 @@ bool aligned4(int Fa, int Fb, const void* a, const void* b) {
     return Fa % 4 == 0 && Fb % 4 == 0 && ((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b)) & 15) == 0;
 }
 
-// Tile of the two launches: 128 wide where the matrix is, 64 otherwise.
-int blocks_for(int extent) { return extent > 64 ? 2 : 1; }
+// Output tile of a launch, by the extents of the two tiled dimensions (m is always "long" for the
+// input gradient, whose rows are the active vertices).
+enum TileShape { T128x128, T128x64, T64x128, T64x64, T128x32, T32x128 };
+TileShape tile_shape(int m, int n) {
+    if (n <= 32 && m > 32) return T128x32;
+    if (m <= 32 && n > 32) return T32x128;
+    if (m > 64) return n > 64 ? T128x128 : T128x64;
+    return n > 64 ? T64x128 : T64x64;
+}
+void tile_dims(TileShape t, int* tm, int* tn) {
+    static const int dims[6][2] = {{128, 128}, {128, 64}, {64, 128}, {64, 64}, {128, 32}, {32, 128}};
+    *tm = dims[t][0];
+    *tn = dims[t][1];
+}
 
 int check_widths(int Fi, int Fo) {
     if (Fi < 1 || Fo < 1 || Fi > kMaxWidth || Fo > kMaxWidth) {
@@ -249,7 +266,8 @@ int row_set(epp_paths* p, int k, hipStream_t s, const int32_t** ids, int64_t* co
 
 // Rows per partial sum: enough chunks to fill the chip a few times over, whole steps each.
 void chunking(int64_t n_rows, int Fi, int Fo, int64_t* rows_per_chunk, int64_t* n_chunks) {
-    const int tm = 64 * blocks_for(Fi), tn = 64 * blocks_for(Fo);
+    int tm, tn;
+    tile_dims(tile_shape(Fi, Fo), &tm, &tn);
     const int64_t tiles = (int64_t)((Fi + tm - 1) / tm) * ((Fo + tn - 1) / tn);
     const int64_t want = std::max<int64_t>(1, 2048 / tiles);
     int64_t per = std::max<int64_t>((n_rows + want - 1) / want, kMinChunkRows);
@@ -286,24 +304,29 @@ extern "C" int epp_weight_gradient(epp_paths_t* paths, int k, const float* Y, in
     int64_t per, chunks;
     chunking(n_rows, F_in, F_out, &per, &chunks);
     if (chunks > 0) {
-        const int bm = blocks_for(F_in), bn = blocks_for(F_out);
-        const dim3 grid((unsigned)chunks, (unsigned)((F_in + 64 * bm - 1) / (64 * bm)),
-                        (unsigned)((F_out + 64 * bn - 1) / (64 * bn)));
+        const TileShape shape = tile_shape(F_in, F_out);
+        int tm, tn;
+        tile_dims(shape, &tm, &tn);
+        const dim3 grid((unsigned)chunks, (unsigned)((F_in + tm - 1) / tm), (unsigned)((F_out + tn - 1) / tn));
         float* part = static_cast<float*>(workspace);
-#define EPP_LAUNCH_WG(BM, BN)                                                                                    \
+        const bool vec = aligned4(F_in, F_out, Y, grad_X);
+#define EPP_LAUNCH_WG(WM, WN, BM, BN)                                                                            \
     do {                                                                                                         \
         if (vec)                                                                                                 \
-            hipLaunchKernelGGL((k_weight_gradient<BM, BN, true>), grid, dim3(kBlock), 0, s, ids, n_rows, per, Y, \
-                               F_in, grad_X, F_out, part);                                                       \
+            hipLaunchKernelGGL((k_weight_gradient<WM, WN, BM, BN, true>), grid, dim3(kBlock), 0, s, ids, n_rows, \
+                               per, Y, F_in, grad_X, F_out, part);                                               \
         else                                                                                                     \
-            hipLaunchKernelGGL((k_weight_gradient<BM, BN, false>), grid, dim3(kBlock), 0, s, ids, n_rows, per, Y, \
-                               F_in, grad_X, F_out, part);                                                       \
+            hipLaunchKernelGGL((k_weight_gradient<WM, WN, BM, BN, false>), grid, dim3(kBlock), 0, s, ids, n_rows, \
+                               per, Y, F_in, grad_X, F_out, part);                                               \
     } while (0)
-        const bool vec = aligned4(F_in, F_out, Y, grad_X);
-        if (bm == 2 && bn == 2) EPP_LAUNCH_WG(2, 2);
-        else if (bm == 2) EPP_LAUNCH_WG(2, 1);
-        else if (bn == 2) EPP_LAUNCH_WG(1, 2);
-        else EPP_LAUNCH_WG(1, 1);
+        switch (shape) {
+            case T128x128: EPP_LAUNCH_WG(2, 2, 2, 2); break;
+            case T128x64: EPP_LAUNCH_WG(2, 2, 2, 1); break;
+            case T64x128: EPP_LAUNCH_WG(2, 2, 1, 2); break;
+            case T64x64: EPP_LAUNCH_WG(2, 2, 1, 1); break;
+            case T128x32: EPP_LAUNCH_WG(4, 1, 1, 1); break;
+            case T32x128: EPP_LAUNCH_WG(1, 4, 1, 1); break;
+        }
 #undef EPP_LAUNCH_WG
     }
     const int64_t total = (int64_t)F_in * F_out;
@@ -323,15 +346,26 @@ extern "C" int epp_input_gradient(epp_paths_t* paths, int k, const float* grad_X
     int64_t n_rows = 0;
     EPP_TRY(row_set(paths, k, s, &ids, &n_rows));
     if (n_rows == 0) return EPP_OK;
-    // rows are the long dimension: 128 of them per tile; 128 columns where F_in has them
-    const int bn = blocks_for(F_in);
-    const dim3 grid((unsigned)((n_rows + 127) / 128), (unsigned)((F_in + 64 * bn - 1) / (64 * bn)));
+    // rows are the long dimension: 128 of them per tile
+    const TileShape shape = tile_shape(1 << 20, F_in);
+    int tm, tn;
+    tile_dims(shape, &tm, &tn);
+    const dim3 grid((unsigned)((n_rows + tm - 1) / tm), (unsigned)((F_in + tn - 1) / tn));
     const bool vec = aligned4(F_out, F_out, grad_X, W);  // both operands are read along F_out
-#define EPP_LAUNCH_IG(BN, VEC)                                                                                  \
-    hipLaunchKernelGGL((k_input_gradient<BN, VEC>), grid, dim3(kBlock), 0, s, ids, n_rows, grad_X, F_out, W, F_in, \
-                       grad_Y)
-    if (bn == 2) { if (vec) EPP_LAUNCH_IG(2, true); else EPP_LAUNCH_IG(2, false); }
-    else { if (vec) EPP_LAUNCH_IG(1, true); else EPP_LAUNCH_IG(1, false); }
+#define EPP_LAUNCH_IG(WM, WN, BM, BN)                                                                              \
+    do {                                                                                                           \
+        if (vec)                                                                                                   \
+            hipLaunchKernelGGL((k_input_gradient<WM, WN, BM, BN, true>), grid, dim3(kBlock), 0, s, ids, n_rows,    \
+                               grad_X, F_out, W, F_in, grad_Y);                                                    \
+        else                                                                                                       \
+            hipLaunchKernelGGL((k_input_gradient<WM, WN, BM, BN, false>), grid, dim3(kBlock), 0, s, ids, n_rows,   \
+                               grad_X, F_out, W, F_in, grad_Y);                                                    \
+    } while (0)
+    switch (shape) {
+        case T128x128: EPP_LAUNCH_IG(2, 2, 2, 2); break;
+        case T128x64: EPP_LAUNCH_IG(2, 2, 2, 1); break;
+        default: EPP_LAUNCH_IG(4, 1, 1, 1); break;  // T128x32
+    }
 #undef EPP_LAUNCH_IG
     EPP_HIP_TRY(hipGetLastError());
     return EPP_OK;

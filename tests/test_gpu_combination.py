@@ -48,7 +48,7 @@ def _input_gradient(paths, k, G, W, poison=77.0):
     return Yg.cpu().numpy()
 
 
-SHAPES = [(1, 1), (3, 7), (16, 16), (41, 16), (16, 47), (64, 64), (65, 33), (128, 16), (130, 70)]
+SHAPES = [(1, 1), (3, 7), (16, 16), (41, 16), (16, 47), (64, 64), (65, 33), (40, 100), (128, 16), (130, 70)]
 
 
 @pytest.mark.parametrize("Fi,Fo", SHAPES)
