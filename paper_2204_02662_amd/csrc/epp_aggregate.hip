@@ -380,17 +380,21 @@ __global__ __launch_bounds__(kBlock) void k_count_hist(const int* __restrict__ c
     __shared__ int h[kCountBins];
     if (threadIdx.x < kCountBins) h[threadIdx.x] = 0;
     __syncthreads();
-    int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    const int k = v < n ? cnt[v] : 0;
-    int bin = k > 0 ? count_bin(k) : -1;
-    // lanes with the same bin add once together (most lanes share a handful of small bins)
-    unsigned long long todo = __ballot(bin >= 0);
-    while (todo) {
-        const int leader = __ffsll((long long)todo) - 1;
-        const int b = __shfl(bin, leader, 64);
-        const unsigned long long same = __ballot(bin == b);
-        if ((threadIdx.x & 63) == leader) atomicAdd(&h[b], __popcll(same));
-        todo &= ~same;
+    // grid-stride, whole wavefronts per iteration (the ballots below need all 64 lanes)
+    const int64_t span = (int64_t)gridDim.x * kBlock;
+    for (int64_t base = (int64_t)blockIdx.x * kBlock + (threadIdx.x & ~63); base < n; base += span) {
+        const int64_t v = base + (threadIdx.x & 63);
+        const int k = v < n ? cnt[v] : 0;
+        const int bin = k > 0 ? count_bin(k) : -1;
+        // lanes with the same bin add once together (most lanes share a handful of small bins)
+        unsigned long long todo = __ballot(bin >= 0);
+        while (todo) {
+            const int leader = __ffsll((long long)todo) - 1;
+            const int b = __shfl(bin, leader, 64);
+            const unsigned long long same = __ballot(bin == b);
+            if ((threadIdx.x & 63) == leader) atomicAdd(&h[b], __popcll(same));
+            todo &= ~same;
+        }
     }
     __syncthreads();
     if (threadIdx.x < kCountBins && h[threadIdx.x]) atomicAdd(&hist[threadIdx.x], (unsigned long long)h[threadIdx.x]);
@@ -554,7 +558,7 @@ int epp_tune_locality(epp_path* p, int F, hipStream_t s, int* log2_slices) {
         const int64_t n_sampled_seg = (n_seg + stride - 1) / stride;
         hipLaunchKernelGGL(k_count_sources, dim3((unsigned)((n_sampled_seg + (kBlock / 64) - 1) / (kBlock / 64))),
                            dim3(kBlock), 0, s, reinterpret_cast<const int2v*>(p->cv.p), p->nnz, stride, cnt.as<int>());
-        hipLaunchKernelGGL(k_count_hist, dim3((unsigned)((p->n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
+        hipLaunchKernelGGL(k_count_hist, dim3((unsigned)std::min<int64_t>((p->n + kBlock - 1) / kBlock, 2048)), dim3(kBlock), 0, s,
                            cnt.as<int>(), p->n, hist.as<unsigned long long>());
         EPP_HIP_TRY(hipGetLastError());
         unsigned long long h[kCountBins];
