@@ -109,6 +109,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-all-active", action="store_true")
     ap.add_argument("--no-combination", action="store_true", help="skip the combination-stage report")
+    ap.add_argument("--cold", action="store_true",
+                    help="also time the epoch with 1 GiB streamed through the caches before every layer launch")
     ap.add_argument("--cpu-budget-s", type=float, default=15.0)
     ap.add_argument("--layers", type=str, default="", help="comma list of layers to run (profiling); default all")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -168,7 +170,7 @@ def main():
 
     path_objs = [paths.path(l) for l in range(L)]
 
-    def timed(run_layer, steps, warmup):
+    def timed(run_layer, steps, warmup, between=None):
         for _ in range(warmup):
             for l in order:
                 run_layer(l)
@@ -178,6 +180,8 @@ def main():
         t = time.perf_counter()
         for s in range(steps):
             for i, l in enumerate(order):
+                if between is not None:
+                    between()  # outside the event pair
                 ev[s][i][0].record()
                 run_layer(l)
                 ev[s][i][1].record()
@@ -309,6 +313,15 @@ def main():
                          "input_gradient_mfma_f32_frac": fl_ / y_ms / 1e9 / 157.3})
             del Y, W, G, Wg, ws
         result["combination_active_rows"] = {"dtype": "f32", "layers": comb}
+
+    # training runs other kernels between two aggregations: the same epoch with the caches flushed
+    # (1 GiB written) before every layer launch; the sum of the per-layer event times is reported
+    if args.cold:
+        scratch = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+        _, cold_layer_ms = timed(lambda l: epp.epp_backward_aggregate(path_objs[l], grad_in[l], grad_out[l]),
+                                 max(3, args.steps // 4), 1, between=lambda: scratch.fill_(1.0))
+        result["partially_active"]["cold_cache_ms_per_epoch"] = sum(cold_layer_ms.values())
+        del scratch
 
     # launch-bound workloads: the same epoch captured once in a HIP graph and replayed
     if ms_partial < 1.0 and not args.layers:
