@@ -138,6 +138,25 @@ int epp_full_aggregate(epp_path_t* full, const float* grad_in, float* grad_out, 
 int epp_ifelse_aggregate(epp_path_t* full, const epp_paths_t* paths, int l, const float* grad_in, float* grad_out,
                          int F, epp_stream_t stream);
 
+/* Execution paths prepared earlier and saved by the caller (the paper's pre-processing scenario,
+ * Sec. 6: paths are built once per (G, V_t, L) and reused by later training runs).  `layers[l]`
+ * holds SG_l in the canonical form that epp_path_export writes; all arrays are device memory and
+ * are copied.  The arrays are checked on the GPU before use (row ids ascending and in range, row
+ * pointer non-decreasing from 0 to nnz with no empty row, columns in range): a violation gives
+ * EPP_ERR_INVALID_ARG or EPP_ERR_OUT_OF_RANGE_ID, never a fault.  That the arrays really are the
+ * paths of some graph is the caller's responsibility.  N^0 comes from train_ids as in epp_prepare,
+ * N^k (k >= 1) from the row ids of SG_{L-k}.  Synchronises `stream` before returning. */
+typedef struct {
+    int64_t n_rows;         /* |N^{L-l}|                              */
+    int64_t nnz;            /* entries, < 2^31                        */
+    const int32_t* row_ids; /* device, n_rows, ascending              */
+    const int32_t* rowptr;  /* device, n_rows + 1                     */
+    const int32_t* col;     /* device, nnz                            */
+    const float* val;       /* device, nnz                            */
+} epp_path_arrays_t;
+int epp_paths_import(int64_t n, int L, const int32_t* train_ids, int64_t n_train, const epp_path_arrays_t* layers,
+                     epp_stream_t stream, epp_paths_t** out);
+
 /* Combination stage of the backward pass restricted to the active rows (Alg. 1, backward
  * loop: W'(l) = Y(l)^T (x) X'(l+1) and Y'(l) = X'(l+1) (x) W(l)^T; by Theorem 1 the rows of
  * X'(l+1) outside N^k, k = L-l-1, are zero and add nothing to either product).  Both run on

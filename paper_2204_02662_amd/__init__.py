@@ -27,7 +27,7 @@ EXPORTED = [
     "epp_path_export", "epp_active_set_export", "epp_select_group_size", "epp_path_set_group_size",
     "epp_backward_aggregate", "epp_full_aggregate", "epp_destroy_paths", "epp_destroy_path",
     "epp_last_error", "epp_paper_linreg_group_size", "epp_ifelse_aggregate",
-    "epp_weight_gradient_workspace", "epp_weight_gradient", "epp_input_gradient",
+    "epp_weight_gradient_workspace", "epp_weight_gradient", "epp_input_gradient", "epp_paths_import",
 ]
 
 
@@ -40,6 +40,11 @@ class EppError(RuntimeError):
 class _Csr(ctypes.Structure):
     _fields_ = [("n", ctypes.c_int64), ("nnz", ctypes.c_int64), ("rowptr", ctypes.c_void_p),
                 ("col", ctypes.c_void_p), ("val", ctypes.c_void_p)]
+
+
+class _PathArrays(ctypes.Structure):
+    _fields_ = [("n_rows", ctypes.c_int64), ("nnz", ctypes.c_int64), ("row_ids", ctypes.c_void_p),
+                ("rowptr", ctypes.c_void_p), ("col", ctypes.c_void_p), ("val", ctypes.c_void_p)]
 
 
 class _PathInfo(ctypes.Structure):
@@ -79,6 +84,7 @@ def load_library() -> ctypes.CDLL:
     lib.epp_weight_gradient_workspace.restype = I64
     lib.epp_weight_gradient.argtypes = [P, I, P, I, P, I, P, P, I64, P]
     lib.epp_input_gradient.argtypes = [P, I, P, I, P, I, P, P]
+    lib.epp_paths_import.argtypes = [I64, I, P, I64, ctypes.POINTER(_PathArrays), P, ctypes.POINTER(P)]
     lib.epp_destroy_paths.argtypes = [P]
     lib.epp_destroy_paths.restype = None
     lib.epp_destroy_path.argtypes = [P]
@@ -279,3 +285,20 @@ def epp_input_gradient(paths: Paths, k: int, grad_X: torch.Tensor, W: torch.Tens
         raise ValueError("shapes: grad_X n x F_out, W F_in x F_out, grad_Y n x F_in")
     _check(load_library().epp_input_gradient(paths._h, k, grad_X.data_ptr(), grad_X.shape[1], W.data_ptr(), W.shape[0],
                                              grad_Y.data_ptr(), _stream()))
+
+
+def epp_paths_import(n: int, train_ids: torch.Tensor, layers) -> Paths:
+    """Handle from saved paths: ``layers[l]`` = (row_ids, rowptr, col, val) device tensors of SG_l in the
+    canonical form that ``Path_.export()`` returns."""
+    _dev(train_ids, torch.int32)
+    arr = (_PathArrays * len(layers))()
+    for l, (row_ids, rowptr, col, val) in enumerate(layers):
+        _dev(row_ids, torch.int32), _dev(rowptr, torch.int32), _dev(col, torch.int32), _dev(val, torch.float32)
+        if rowptr.numel() != row_ids.numel() + 1 or col.numel() != val.numel():
+            raise ValueError(f"layer {l}: inconsistent array lengths")
+        arr[l] = _PathArrays(row_ids.numel(), col.numel(), row_ids.data_ptr(), rowptr.data_ptr(), col.data_ptr(),
+                             val.data_ptr())
+    out = ctypes.c_void_p()
+    _check(load_library().epp_paths_import(n, len(layers), train_ids.data_ptr(), train_ids.numel(), arr, _stream(),
+                                           ctypes.byref(out)))
+    return Paths(out.value)

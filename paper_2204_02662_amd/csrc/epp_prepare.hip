@@ -373,6 +373,28 @@ int compact_bitmap(const DevBuf& bitmap, int64_t n, const int* newptr, int total
     return EPP_OK;
 }
 
+// Checks of imported path arrays: bit 0 structure (ids not ascending, pointer decreasing, empty
+// row, wrong end points), bit 1 an id outside [0, n).  Also sets the bitmap of the row set.
+__global__ __launch_bounds__(kBlock) void k_check_rows(const int32_t* __restrict__ row_ids,
+                                                       const int32_t* __restrict__ rowptr, int64_t n_rows, int64_t nnz,
+                                                       int64_t n, unsigned int* __restrict__ bitmap32,
+                                                       int* __restrict__ err) {
+    const int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (r == 0 && (rowptr[0] != 0 || rowptr[n_rows] != nnz)) atomicOr(err, 1);
+    if (r >= n_rows) return;
+    const int32_t v = row_ids[r];
+    if (v < 0 || v >= n) { atomicOr(err, 2); return; }
+    if (r > 0 && row_ids[r - 1] >= v) atomicOr(err, 1);
+    if (rowptr[r + 1] <= rowptr[r]) atomicOr(err, 1);
+    atomicOr(&bitmap32[v >> 5], 1u << (v & 31));
+}
+
+__global__ __launch_bounds__(kBlock) void k_check_cols(const int32_t* __restrict__ col, int64_t nnz, int64_t n,
+                                                       int* __restrict__ err) {
+    const int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (e < nnz && (col[e] < 0 || col[e] >= n)) atomicOr(err, 2);
+}
+
 }  // namespace
 
 int epp_path_finish(epp_path* p, hipStream_t s) {
@@ -579,6 +601,93 @@ extern "C" int epp_prepare_full(const epp_csr_t* g, epp_stream_t stream, epp_pat
     EPP_HIP_TRY(hipStreamSynchronize(s));
     guard.p = nullptr;
     *out = p;
+    return EPP_OK;
+}
+
+extern "C" int epp_paths_import(int64_t n, int L, const int32_t* train_ids, int64_t n_train,
+                                const epp_path_arrays_t* layers, epp_stream_t stream, epp_paths_t** out) {
+    if (!out) { epp_set_error("out is NULL"); return EPP_ERR_INVALID_ARG; }
+    *out = nullptr;
+    if (L < 1 || !layers) { epp_set_error("L must be >= 1 and layers non-NULL"); return EPP_ERR_INVALID_ARG; }
+    if (n < 0 || n_train < 0 || (n_train > 0 && !train_ids)) { epp_set_error("bad sizes"); return EPP_ERR_INVALID_ARG; }
+    if (n >= 0x40000000ll) { epp_set_error("graph too large: n=%lld (limit 2^30-1)", (long long)n); return EPP_ERR_TOO_LARGE; }
+    for (int l = 0; l < L; ++l) {
+        const epp_path_arrays_t& a = layers[l];
+        if (a.n_rows < 0 || a.n_rows > n || a.nnz < 0 || !a.rowptr || (a.n_rows > 0 && !a.row_ids) ||
+            (a.nnz > 0 && (!a.col || !a.val)) || (a.n_rows == 0 && a.nnz != 0)) {
+            epp_set_error("layer %d: inconsistent sizes or NULL arrays", l);
+            return EPP_ERR_INVALID_ARG;
+        }
+        if (a.nnz >= 0x7FFFFFFFll) { epp_set_error("layer %d: nnz=%lld (limit 2^31-1)", l, (long long)a.nnz); return EPP_ERR_TOO_LARGE; }
+    }
+    hipStream_t s = (hipStream_t)stream;
+    const int64_t n_words = (n + 63) / 64;
+    HostScalars hs;
+    EPP_TRY(hs.init());
+    epp_paths* P = new epp_paths();
+    struct Guard { epp_paths* p; ~Guard() { delete p; } } guard{P};
+    P->L = L;
+    P->n = n;
+    P->bitmaps.resize(L + 1);
+    P->set_size.assign(L + 1, 0);
+    P->path.assign(L, nullptr);
+    for (int k = 0; k <= L; ++k) {
+        EPP_TRY(P->bitmaps[k].alloc((size_t)n_words * 8));
+        EPP_HIP_TRY(hipMemsetAsync(P->bitmaps[k].p, 0, P->bitmaps[k].bytes, s));
+    }
+    DevBuf tile_cnt, tile_base, dev_total, err;
+    const size_t tiles = std::max<size_t>(grid_for(n_words, kWordsPerTile), 1);
+    EPP_TRY(tile_cnt.alloc(tiles * 4));
+    EPP_TRY(tile_base.alloc(tiles * 4));
+    EPP_TRY(dev_total.alloc(sizeof(long long)));
+    EPP_TRY(err.alloc(2 * sizeof(int)));  // [0]: path arrays, [1]: training ids
+    EPP_HIP_TRY(hipMemsetAsync(err.p, 0, 2 * sizeof(int), s));
+    if (n_train > 0)
+        hipLaunchKernelGGL(k_mark_training, dim3(grid_for(n_train, kBlock)), dim3(kBlock), 0, s, train_ids, n_train, n,
+                           P->bitmaps[0].as<unsigned int>(), err.as<int>() + 1);
+    for (int l = 0; l < L; ++l) {
+        const epp_path_arrays_t& a = layers[l];
+        hipLaunchKernelGGL(k_check_rows, dim3(std::max(grid_for(a.n_rows, kBlock), 1u)), dim3(kBlock), 0, s, a.row_ids,
+                           a.rowptr, a.n_rows, a.nnz, n, P->bitmaps[L - l].as<unsigned int>(), err.as<int>());
+        if (a.nnz > 0)
+            hipLaunchKernelGGL(k_check_cols, dim3(grid_for(a.nnz, kBlock)), dim3(kBlock), 0, s, a.col, a.nnz, n,
+                               err.as<int>());
+    }
+    EPP_HIP_TRY(hipGetLastError());
+    int herr2[2] = {0, 0};
+    EPP_HIP_TRY(hipMemcpyAsync(herr2, err.p, sizeof(herr2), hipMemcpyDeviceToHost, s));
+    EPP_HIP_TRY(hipStreamSynchronize(s));
+    const int herr = herr2[0] | (herr2[1] ? 2 : 0);
+    if (herr & 2) { epp_set_error("an id lies outside [0, %lld)", (long long)n); return EPP_ERR_OUT_OF_RANGE_ID; }
+    if (herr & 1) { epp_set_error("path arrays are not in canonical form"); return EPP_ERR_INVALID_ARG; }
+    EPP_TRY(compact_bitmap(P->bitmaps[0], n, nullptr, 0, nullptr, nullptr, &P->set_size[0], tile_cnt, tile_base,
+                           dev_total, hs, s));
+    for (int l = L - 1; l >= 0; --l) {
+        const epp_path_arrays_t& a = layers[l];
+        const int k = L - l - 1;
+        epp_path* p = new epp_path();
+        P->path[l] = p;
+        p->n = n;
+        p->n_rows = p->n_stream_rows = a.n_rows;
+        p->nnz = a.nnz;
+        p->n_src = P->set_size[k];
+        P->set_size[k + 1] = a.n_rows;
+        EPP_TRY(p->row_ids.alloc((size_t)a.n_rows * 4));
+        EPP_TRY(p->rowptr.alloc((size_t)(a.n_rows + 1) * 4));
+        EPP_TRY(p->cv.alloc((size_t)a.nnz * sizeof(int2)));
+        if (a.n_rows > 0)
+            EPP_HIP_TRY(hipMemcpyAsync(p->row_ids.p, a.row_ids, (size_t)a.n_rows * 4, hipMemcpyDeviceToDevice, s));
+        EPP_HIP_TRY(hipMemcpyAsync(p->rowptr.p, a.rowptr, (size_t)(a.n_rows + 1) * 4, hipMemcpyDeviceToDevice, s));
+        if (a.nnz > 0) {
+            hipLaunchKernelGGL(k_interleave, dim3(grid_for(a.nnz, kBlock)), dim3(kBlock), 0, s, a.col, a.val, a.nnz,
+                               p->cv.as<int2>());
+            EPP_HIP_TRY(hipGetLastError());
+        }
+        EPP_TRY(epp_path_finish(p, s));
+    }
+    EPP_HIP_TRY(hipStreamSynchronize(s));
+    guard.p = nullptr;
+    *out = P;
     return EPP_OK;
 }
 

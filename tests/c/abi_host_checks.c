@@ -37,6 +37,7 @@ int main(void) {
     g.n = -1;
     CHECK(epp_prepare_full(&g, NULL, &full) == EPP_ERR_INVALID_ARG);
 
+    CHECK(epp_paths_import(10, 1, NULL, 0, NULL, NULL, &paths) == EPP_ERR_INVALID_ARG);
     CHECK(epp_num_layers(NULL) == EPP_ERR_INVALID_ARG);
     CHECK(epp_get_path(NULL, 0) == NULL);
     CHECK(epp_select_group_size(NULL, 16) == EPP_ERR_INVALID_ARG);

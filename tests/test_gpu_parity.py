@@ -298,3 +298,51 @@ def test_randomised_shapes():
             ie = run_ifelse(full, paths, l, X)
             assert np.all(ie[~rows] == 123.0)
             assert_close(ie[rows], want[rows], f"case {case} l={l} if-else")
+
+
+def test_import_of_saved_paths():
+    """Pre-processing scenario: paths exported once, imported into a fresh handle, give the same
+    canonical arrays, active sets and gradients; malformed arrays are refused, not executed."""
+    g = graphgen.random_graph("rmat", 3000, seed=95, raw_draws=40_000)
+    train = graphgen.training_set(g.n, 50, 96)
+    L, F = 3, 24
+    sets_o, paths_o = oprep(g, train, L)
+    paths = gpu_prepare(g, train, L)
+    saved = [paths.path(l).export() for l in range(L)]
+    d = dev()
+    ids = torch.from_numpy(np.ascontiguousarray(train, np.int32)).to(d)
+    again = epp.epp_paths_import(g.n, ids, saved)
+    assert_paths_bit_exact(again, sets_o, paths_o, L)
+    full = gpu_prepare_full(g)
+    for l in range(L):
+        X = graphgen.normal_rows(g.n, F, sets_o[L - l - 1], 97 + l)
+        want = oracle.path_aggregate(g.n, paths_o[l], X)
+        rows = sets_o[L - l].astype(bool)
+        got = run_partial(again.path(l), X, poison=4.0)
+        assert np.all(got[~rows] == 4.0)
+        assert_close(got[rows], want[rows], f"imported layer {l}")
+        assert_close(run_ifelse(full, again, l, X)[rows], want[rows], f"if-else on imported sets, layer {l}")
+    # malformed inputs
+    row_ids, rowptr, col, val = saved[0]
+    bad = row_ids.clone()
+    bad[[0, 1]] = bad[[1, 0]]                                      # not ascending
+    with pytest.raises(epp.EppError) as e:
+        epp.epp_paths_import(g.n, ids, [(bad, rowptr, col, val)] + saved[1:])
+    assert e.value.code == epp.EPP_ERR_INVALID_ARG
+    bad = col.clone()
+    bad[5] = g.n                                                   # column out of range
+    with pytest.raises(epp.EppError) as e:
+        epp.epp_paths_import(g.n, ids, [(row_ids, rowptr, bad, val)] + saved[1:])
+    assert e.value.code == epp.EPP_ERR_OUT_OF_RANGE_ID
+    bad = rowptr.clone()
+    bad[-1] += 1                                                   # does not end at nnz
+    with pytest.raises(epp.EppError) as e:
+        epp.epp_paths_import(g.n, ids, [(row_ids, bad, col, val)] + saved[1:])
+    assert e.value.code == epp.EPP_ERR_INVALID_ARG
+    bad = rowptr.clone()
+    bad[3] = bad[2]                                                # an empty row
+    with pytest.raises(epp.EppError):
+        epp.epp_paths_import(g.n, ids, [(row_ids, bad, col, val)] + saved[1:])
+    with pytest.raises(epp.EppError) as e:                         # training id out of range
+        epp.epp_paths_import(g.n, torch.tensor([g.n], dtype=torch.int32, device=d), saved)
+    assert e.value.code == epp.EPP_ERR_OUT_OF_RANGE_ID
