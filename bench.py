@@ -222,6 +222,10 @@ def main():
         "bound": "hbm", "kernel": f"k_aggregate (layer l={dom['l']}, F={dom['F']})",
         "achieved": dom["roofline_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": dom["roofline_frac"], "traffic": traffic,
+        # the same launch by the counters: HBM-side bytes actually moved per second (rises when caching gets
+        # worse; evidence, not an objective)
+        "traffic_GBs": traffic / dom["ms"] / 1e6 if traffic else None,
+        "traffic_frac_of_peak": traffic / dom["ms"] / 1e6 / HBM_PEAK_GBS if traffic else None,
     }
 
     result = {
