@@ -397,9 +397,10 @@ __global__ __launch_bounds__(kBlock) void k_check_cols(const int32_t* __restrict
 
 }  // namespace
 
-int epp_path_finish(epp_path* p, hipStream_t s) {
+int epp_path_finish(epp_path* p, hipStream_t s, void* stats_scratch) {
     DevBuf stats;
-    EPP_TRY(stats.alloc((EPP_NCLASS + 1) * sizeof(unsigned long long)));
+    if (stats_scratch) stats.view(stats_scratch, (EPP_NCLASS + 1) * sizeof(unsigned long long));
+    else EPP_TRY(stats.alloc((EPP_NCLASS + 1) * sizeof(unsigned long long)));
     EPP_HIP_TRY(hipMemsetAsync(stats.p, 0, stats.bytes, s));
     if (p->n_rows > 0) {
         // canonical rows: the all-active graph counts its empty rows too
@@ -452,15 +453,22 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
         EPP_HIP_TRY(hipMemsetAsync(P->bitmaps[k].p, 0, P->bitmaps[k].bytes, s));
     }
 
-    DevBuf mask, seg_base, tile_cnt, tile_base, newptr, dev_total, err;
-    EPP_TRY(mask.alloc((size_t)n_seg * 8));
-    EPP_TRY(seg_base.alloc((size_t)n_seg * 4));
+    // all temporaries of the construction come from one allocation
+    DevBuf mask, seg_base, tile_cnt, tile_base, newptr, dev_total, err, stats;
     const size_t max_tiles = std::max<size_t>(std::max(edge_tiles, word_tiles), 1);
-    EPP_TRY(tile_cnt.alloc(max_tiles * 4));
-    EPP_TRY(tile_base.alloc(max_tiles * 4));
-    EPP_TRY(newptr.alloc((size_t)(n + 1) * 4));
-    EPP_TRY(dev_total.alloc(sizeof(long long)));
-    EPP_TRY(err.alloc(sizeof(int)));
+    const size_t stats_bytes = (EPP_NCLASS + 1) * sizeof(unsigned long long);
+    DevArena arena;
+    EPP_TRY(arena.reserve(DevArena::rounded((size_t)n_seg * 8) + DevArena::rounded((size_t)n_seg * 4) +
+                          2 * DevArena::rounded(max_tiles * 4) + DevArena::rounded((size_t)(n + 1) * 4) +
+                          2 * DevArena::rounded(8) + DevArena::rounded(stats_bytes)));
+    arena.take(&mask, (size_t)n_seg * 8);
+    arena.take(&seg_base, (size_t)n_seg * 4);
+    arena.take(&tile_cnt, max_tiles * 4);
+    arena.take(&tile_base, max_tiles * 4);
+    arena.take(&newptr, (size_t)(n + 1) * 4);
+    arena.take(&dev_total, sizeof(long long));
+    arena.take(&err, sizeof(int));
+    arena.take(&stats, stats_bytes);
     EPP_HIP_TRY(hipMemsetAsync(err.p, 0, sizeof(int), s));
     EPP_HIP_TRY(hipMemsetAsync(newptr.p, 0, newptr.bytes, s));
 
@@ -515,7 +523,7 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
                                &P->set_size[k + 1], tile_cnt, tile_base, dev_total, hs, s));
         p->n_rows = P->set_size[k + 1];
         p->n_stream_rows = p->n_rows;  // every row of a path has at least one entry
-        EPP_TRY(epp_path_finish(p, s));
+        EPP_TRY(epp_path_finish(p, s, stats.p));
         // Fixed point: N^{k+1} == N^k means every further set is the same set, so every deeper
         // layer (rows and sources both equal to it) has exactly this path; share it.
         if (k + 1 < L && P->set_size[k + 1] == P->set_size[k]) {
