@@ -544,13 +544,19 @@ int epp_tune_locality(epp_path* p, int F, hipStream_t s, int* log2_slices) {
     const int forced_slices = env_int("EPP_TUNE_LOG2_SLICES", -1);
     *log2_slices = forced_slices >= 0 ? forced_slices : 0;
     int thr = 0;
-    DevBuf cnt;
+    DevArena arena;
+    DevBuf cnt, hot;
     // (measured useful for rows of 256 bytes and more; at F = 47 the extra branch costs 3 %)
     if (budget_mb > 0 && p->nnz > 0 && p->n_src > rows_budget && (int64_t)F * 4 >= 256) {
-        EPP_TRY(cnt.alloc((size_t)p->n * 4));
+        // counts, histogram and hot bitmap share one allocation
+        const size_t hot_bytes = (size_t)((p->n + 63) / 64) * 8;
+        EPP_TRY(arena.reserve(DevArena::rounded((size_t)p->n * 4) + DevArena::rounded(kCountBins * sizeof(unsigned long long)) +
+                              DevArena::rounded(hot_bytes)));
+        arena.take(&cnt, (size_t)p->n * 4);
         EPP_HIP_TRY(hipMemsetAsync(cnt.p, 0, cnt.bytes, s));
         DevBuf hist;
-        EPP_TRY(hist.alloc(kCountBins * sizeof(unsigned long long)));
+        arena.take(&hist, kCountBins * sizeof(unsigned long long));
+        arena.take(&hot, hot_bytes);
         EPP_HIP_TRY(hipMemsetAsync(hist.p, 0, hist.bytes, s));
         // at most ~16 M sampled entries
         const int64_t n_seg = (p->nnz + 63) / 64;
@@ -589,9 +595,7 @@ int epp_tune_locality(epp_path* p, int F, hipStream_t s, int* log2_slices) {
         }
     }
     if (thr == p->cold_thr) return EPP_OK;
-    DevBuf hot;
     if (thr > 0) {
-        EPP_TRY(hot.alloc((size_t)((p->n + 63) / 64) * 8));
         hipLaunchKernelGGL(k_hot_bitmap, dim3((unsigned)((p->n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
                            cnt.as<int>(), p->n, thr, hot.as<unsigned long long>());
     }
