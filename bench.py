@@ -42,15 +42,15 @@ def edge_bytes(R: int, nnz: int, F: int) -> int:
 
 
 def read_traffic(workload: str):
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter
-    summary (profiles/hbm_traffic.txt: lines `<workload> <layer> <fetch_bytes> <write_bytes>`)."""
+    """(HBM bytes per launch, L2 hit rate) of the aggregation kernel per layer, from the committed rocprofv3
+    counter summary (profiles/hbm_traffic.txt: lines `<workload> <layer> <fetch_bytes> <write_bytes> <l2 hit rate>`)."""
     f = ROOT / "profiles" / "hbm_traffic.txt"
     out = {}
     if f.exists():
         for line in f.read_text().splitlines():
             parts = line.split()
-            if len(parts) == 4 and parts[0] == workload:
-                out[int(parts[1])] = float(parts[2]) + float(parts[3])
+            if len(parts) >= 4 and parts[0] == workload:
+                out[int(parts[1])] = (float(parts[2]) + float(parts[3]), float(parts[4]) if len(parts) > 4 else None)
     return out
 
 
@@ -226,7 +226,10 @@ def main():
             "gather_GBs": bedge / ms / 1e6 if ms > 0 else None,
         })
     dom = max(layers, key=lambda d: d["ms"])
-    traffic = read_traffic(cfg.name).get(dom["l"])
+    traffic, l2_hit = read_traffic(cfg.name).get(dom["l"], (None, None))
+    # the machine's own random-row gather rate (tools/gather_rate.hip): 235 G lines/s from L2, 60 G lines/s beyond
+    lines = dom["nnz"] * ((dom["F"] * 4 + 127) // 128)
+    model_ms = lines * ((1.0 - l2_hit) / 60e9 + l2_hit / 235e9) * 1e3 if l2_hit is not None else None
     roofline = {
         "bound": "hbm", "kernel": f"k_aggregate (layer l={dom['l']}, F={dom['F']})",
         "achieved": dom["roofline_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -235,6 +238,9 @@ def main():
         # worse; evidence, not an objective)
         "traffic_GBs": traffic / dom["ms"] / 1e6 if traffic else None,
         "traffic_frac_of_peak": traffic / dom["ms"] / 1e6 / HBM_PEAK_GBS if traffic else None,
+        # time the gathered 128-byte lines alone would take at the measured gather rates of this chip
+        "gather_rate_model": {"lines": lines, "l2_hit_rate": l2_hit, "model_ms": model_ms,
+                              "measured_over_model": dom["ms"] / model_ms if model_ms else None},
     }
 
     result = {
