@@ -54,12 +54,13 @@ typedef struct {
     int64_t n_src;        /* |N^{L-l-1}|: size of the source set                            */
     int64_t max_len;      /* longest filtered neighbour list                                */
     int64_t len_hist[32]; /* rows per length class c: len <= 1 -> 0, else ceil(log2(len))   */
-    int64_t bytes;        /* device bytes held by the path (canonical arrays + schedules)   */
+    int64_t bytes;        /* device bytes held by the path (canonical arrays + schedules,
+                             the per-group partial rows of every width used included)     */
     /* schedule most recently used / built (0 if none yet) */
     int32_t sched_F;        /* gradient width it was built for                              */
     int32_t group_size;     /* gs: entries per group (Sec. 2.2, Sec. 5)                     */
     int64_t n_groups;       /* ceil(nnz / gs)                                               */
-    int64_t n_split_rows;   /* rows cut by a group boundary (written back with atomics)     */
+    int64_t n_split_rows;   /* rows cut by a group boundary (summed from per-group pieces)  */
 } epp_path_info_t;
 
 /* Execution path preparing (Sec. 4): computes N^k for k = 0..L (Theorem 1) by backward
@@ -120,6 +121,9 @@ int epp_path_set_group_size(epp_path_t* p, int F, int gs, epp_stream_t stream);
  *   grad_in, grad_out   device, row-major n x F fp32 (leading dimension F), not aliased
  *   rows of grad_out outside the path are NOT touched (zero them once; the active sets never
  *   change across epochs); rows of grad_in outside the source set are never read.
+ * A row whose list is cut by group boundaries is summed from per-group partial rows kept in the
+ * handle (2 * n_groups * F floats per width, allocated at the first call with that width), in
+ * group order and without floating-point atomics: equal inputs give bit-identical results.
  * Asynchronous on `stream` except for the first call with a new (path, F), which builds the
  * group schedule and synchronises once. */
 int epp_backward_aggregate(epp_path_t* p, const float* grad_in, float* grad_out, int F, epp_stream_t stream);

@@ -14,11 +14,12 @@
 //   * the slot streams its group's (column, weight) pairs U at a time, issues the U row
 //     gathers back to back, and prefetches the next U pairs while they are in flight;
 //   * the last entry of every row carries a flag (sign bit of the column id).  When a slot
-//     meets it, the accumulated row is written: with a plain store if the whole row lies
-//     inside the group, with hardware fp32 atomics if the row is shared with a neighbouring
-//     group (rows cut by a group boundary are zeroed by a small kernel first);
+//     meets it, the accumulated row is written to the output if the whole row lies inside the
+//     group; the part of a row cut by a group boundary goes to one of the group's two
+//     partial-row slots instead, and a small second kernel adds the pieces of every cut row in
+//     group order.  No floating-point atomics: results are bit-reproducible;
 //   * no cross-lane reduction is needed: lanes split the feature dimension, never a row's
-//     neighbours, so the only cross-group combination is the atomic write-back.
+//     neighbours, so the only cross-group combination is that sum of partial rows.
 
 #include <algorithm>
 #include <cmath>
@@ -69,8 +70,7 @@ __global__ __launch_bounds__(kBlock) void k_sched_groups(const int32_t* __restri
 }
 
 // ------------------------------------------------------------------------- aggregation
-// Zero the rows that receive atomics (rows cut by a group boundary, given as streamed-row
-// indices) or, for the all-active graph, the vertices whose lists are empty.
+// Zero the given rows (all-active graph: the vertices whose lists are empty).
 __global__ __launch_bounds__(kBlock) void k_zero_rows(const int32_t* __restrict__ rows, int64_t n_rows,
                                                       const int32_t* __restrict__ row_ids, int F,
                                                       const unsigned int* __restrict__ only_bits,
@@ -98,25 +98,55 @@ struct AggArgs {
     int gs;
     int log2ns;                // feature slices spread over the XCDs (1 << log2ns of them)
     int has_cold;              // some entries carry the cold flag (host-side kernel choice)
+    float* pieces;             // partial rows of the groups, [n_groups][2][F]
     // if-else selective scheduling only: membership bitmaps of the layer's rows and sources
     const unsigned int* row_bits;
     const unsigned int* src_bits;
 };
 
 template <int VEC>
-__device__ __forceinline__ void write_row(float* __restrict__ o, const float (&acc)[VEC], bool atomic) {
-    if (atomic) {
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) unsafeAtomicAdd(o + i, acc[i]);
+__device__ __forceinline__ void write_row(float* __restrict__ o, const float (&acc)[VEC]) {
+    typename VecT<VEC>::type r;
+    if constexpr (VEC == 1) {
+        r = acc[0];
     } else {
-        typename VecT<VEC>::type r;
-        if constexpr (VEC == 1) {
-            r = acc[0];
-        } else {
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) r[i] = acc[i];
+        for (int i = 0; i < VEC; ++i) r[i] = acc[i];
+    }
+    __builtin_nontemporal_store(r, reinterpret_cast<typename VecT<VEC>::type*>(o));
+}
+
+// out[vertex(r), :] = sum of the partial rows of cut row r, in group order: the row starts in
+// group g0 (whose end-of-group slot holds its head), runs through whole groups (end-of-group
+// slots) and ends in group g1 (whose start-of-group slot holds its tail).  Fp lanes (a power of
+// two >= min(F, 64)) work on one row, eight independent loads at a time; the additions stay in
+// group order, so the result does not depend on the launch shape.
+__global__ __launch_bounds__(kBlock) void k_combine_cut_rows(const int32_t* __restrict__ cut_rows, int64_t n_cut,
+                                                             const int32_t* __restrict__ rowptr,
+                                                             const int32_t* __restrict__ row_ids, int gs, int F,
+                                                             int log2Fp, const float* __restrict__ pieces,
+                                                             const unsigned int* __restrict__ only_bits,
+                                                             float* __restrict__ out) {
+    const int Fp = 1 << log2Fp;
+    const int64_t k = ((int64_t)blockIdx.x * kBlock + threadIdx.x) >> log2Fp;
+    if (k >= n_cut) return;
+    const int32_t r = cut_rows[k];
+    const int32_t v = row_ids ? row_ids[r] : r;
+    if (only_bits && !((only_bits[v >> 5] >> (v & 31)) & 1u)) return;
+    const int64_t g0 = rowptr[r] / gs, g1 = ((int64_t)rowptr[r + 1] - 1) / gs;
+    for (int f = threadIdx.x & (Fp - 1); f < F; f += Fp) {
+        float sum = 0.0f;
+        int64_t g = g0;
+        for (; g + 8 <= g1; g += 8) {
+            float x[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) x[i] = pieces[((g + i) * 2 + 1) * F + f];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) sum += x[i];
         }
-        __builtin_nontemporal_store(r, reinterpret_cast<typename VecT<VEC>::type*>(o));
+        for (; g < g1; ++g) sum += pieces[(g * 2 + 1) * F + f];
+        sum += pieces[(g1 * 2) * F + f];
+        out[(size_t)v * F + f] = sum;
     }
 }
 
@@ -129,8 +159,11 @@ __device__ __forceinline__ void write_row(float* __restrict__ o, const float (&a
 // The next 4T pairs are fetched into registers while the current ones are consumed.  The
 // staging area is private to the wavefront (LDS operations of one wavefront execute in
 // order), so no workgroup barrier is involved.
+//
+// The membership tests of the if-else variant cost a few registers, enough to lose a
+// wavefront per SIMD; its register budget is capped to the occupancy of the plain kernel.
 template <int VEC, int LOG2T, int U_, bool IFELSE, bool COLD>
-__global__ __launch_bounds__(kBlock) void k_aggregate(AggArgs a) {
+__global__ __launch_bounds__(kBlock, IFELSE ? (COLD ? 4 : 5) : 1) void k_aggregate(AggArgs a) {
     constexpr int T = 1 << LOG2T;
     constexpr int S = 4 * T;              // pairs staged per slot
     constexpr int U = U_ < S ? U_ : S;    // S is a multiple of U
@@ -152,6 +185,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(AggArgs a) {
     const int slice = xcd & (ns - 1);
     const int64_t qb = ((int64_t)(blockIdx.x >> 3) << (3 - a.log2ns)) + (xcd >> a.log2ns);
     const int64_t g = qb * (kBlock >> LOG2T) + (threadIdx.x >> LOG2T);
+    const unsigned gi = (unsigned)g;  // n_groups < 2^31
     const bool has = g < a.n_groups;  // slots past the end idle through the loop (no early exit: LDS order)
     const int t = threadIdx.x & (T - 1);
     const int64_t j0 = has ? g * a.gs : 0;
@@ -163,7 +197,6 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(AggArgs a) {
         const int f = f0 + (slice * T + t) * VEC;
         const bool fok = f < a.F;
         const float* __restrict__ src = a.in + (fok ? f : 0);
-        float* __restrict__ dstbase = a.out + f;
         // first 4T pairs of the group: issued before anything that depends on the group table,
         // so that the two load chains (pairs -> gathers, group row -> vertex id) overlap
         // (pairs past the end of the group are clamped loads; they are neutralised only when they
@@ -267,7 +300,16 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(AggArgs a) {
                     if (e[u].x < 0) {  // last entry of row r
                         bool wr = fok;
                         if constexpr (IFELSE) wr = fok && ((a.row_bits[v >> 5] >> (v & 31)) & 1u);
-                        if (wr) write_row<VEC>(dstbase + (size_t)v * (size_t)a.F, acc, shared);
+                        // a row that began in an earlier group: its tail goes to the group's first slot
+                        if (shared) {
+                            // (the slot's address is formed here, from a value the compiler cannot
+                            // trace, so that it is not kept in registers across the whole loop)
+                            unsigned gl = gi;
+                            asm volatile("" : "+v"(gl));
+                            if (fok) write_row<VEC>(a.pieces + (size_t)(2 * gl) * (size_t)a.F + f, acc);
+                        } else if (wr) {
+                            write_row<VEC>(a.out + ((size_t)v * (size_t)a.F + f), acc);
+                        }
 #pragma unroll
                         for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
                         shared = false;
@@ -292,9 +334,9 @@ __global__ __launch_bounds__(kBlock) void k_aggregate(AggArgs a) {
         }
         // the group ends inside a row: that row continues in the next group
         if (open && fok) {
-            bool wr = true;
-            if constexpr (IFELSE) wr = (a.row_bits[v >> 5] >> (v & 31)) & 1u;
-            if (wr) write_row<VEC>(dstbase + (size_t)v * (size_t)a.F, acc, true);
+            unsigned gl = gi;
+            asm volatile("" : "+v"(gl));
+            write_row<VEC>(a.pieces + (size_t)(2 * gl + 1) * (size_t)a.F + f, acc);
         }
     }
 }
@@ -426,8 +468,8 @@ __global__ __launch_bounds__(kBlock) void k_mark_cold(int2v* __restrict__ cv, in
 //
 // On this machine a group is a fixed-cost unit (gs gathers of one row fragment each), so
 // load balance no longer depends on the degree distribution; what the group size trades is
-// (a) the per-group cost and the atomic write-back and zeroing of the rows cut by group
-// boundaries, which fall as gs grows, against (b) having enough groups in flight, which
+// (a) the per-group cost and the partial rows of the rows cut by group boundaries (written by the
+// groups, added by a second kernel), which fall as gs grows, against (b) having enough groups in flight, which
 // matters for small paths.  As in Sec. 5 the size is predicted by a linear regression on
 // structural features, learned from a generated corpus: 72 R-MAT and Chung-Lu graphs (2^12 to
 // 2^21 vertices, average degree 4 to 64, 1 % and 10 % training vertices), two paths each,
@@ -488,11 +530,8 @@ int epp_launch_aggregate(epp_path* p, Schedule* sc, int log2_slices, const float
     while (log2ns > 0 && ((log2T - log2ns) < 0 || ((vec * 4) << (log2T - log2ns)) < 128)) --log2ns;
     log2T -= log2ns;
     const int32_t* row_ids = p->row_ids.p ? p->row_ids.as<int32_t>() : nullptr;
-    if (sc->n_split_rows > 0) {
-        const int64_t total = sc->n_split_rows * F;
-        hipLaunchKernelGGL(k_zero_rows, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
-                           sc->cut_rows.as<int32_t>(), sc->n_split_rows, row_ids, F, row_bits, out);
-    }
+    float* pieces = sc->pieces_for(F);
+    if (sc->n_split_rows > 0 && !pieces) { epp_set_error("no partial-row buffer for F=%d", F); return EPP_ERR_INVALID_ARG; }
     if (p->n_empty_rows > 0 && !row_bits) {  // all-active graph: vertices without any entry become zero
         const int64_t total = p->n_empty_rows * F;
         hipLaunchKernelGGL(k_zero_rows, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
@@ -513,12 +552,20 @@ int epp_launch_aggregate(epp_path* p, Schedule* sc, int log2_slices, const float
         a.gs = sc->gs;
         a.log2ns = log2ns;
         a.has_cold = p->cold_thr > 0;
+        a.pieces = pieces;
         a.row_bits = row_bits;
         a.src_bits = src_bits;
         // gathers in flight per lane: 8 x 16 bytes, or 16 narrower ones
         if (vec == 4) launch_vec<4, 8>(log2T, s, a);
         else if (vec == 2) launch_vec<2, 16>(log2T, s, a);
         else launch_vec<1, 16>(log2T, s, a);
+    }
+    if (sc->n_split_rows > 0) {
+        const int log2Fp = std::min(ceil_log2(F), 6);
+        const int64_t total = sc->n_split_rows << log2Fp;
+        hipLaunchKernelGGL(k_combine_cut_rows, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
+                           sc->cut_rows.as<int32_t>(), sc->n_split_rows, p->rowptr.as<int32_t>(), row_ids, sc->gs, F,
+                           log2Fp, pieces, row_bits, out);
     }
     EPP_HIP_TRY(hipGetLastError());
     return EPP_OK;

@@ -28,6 +28,7 @@ int ensure_schedule(epp_path* p, int F, hipStream_t s, epp_path::WidthCfg** out)
         const int gs = w->forced_gs > 0 ? w->forced_gs : epp_default_group_size(p, F);
         Schedule* sc = find_schedule(p, gs);
         if (!sc) EPP_TRY(epp_build_schedule(p, gs, s, &sc));
+        EPP_TRY(sc->ensure_pieces(F));
         EPP_TRY(epp_tune_locality(p, F, s, &w->log2_slices));
         w->sched = sc;
     }

@@ -92,10 +92,34 @@ struct DevArena {
 struct Schedule {
     int gs = 0;
     int64_t n_groups = 0;
-    int64_t n_split_rows = 0;  // rows cut by a group boundary (written with atomics)
+    int64_t n_split_rows = 0;  // rows cut by a group boundary (summed from the groups' partial rows)
     DevBuf group_row;          // int32[n_groups] row holding the group's first entry; bit 31: starts inside it
-    DevBuf cut_rows;           // int32[n_split_rows] (path-row indices) zeroed before every launch
-    size_t bytes() const { return group_row.bytes + cut_rows.bytes; }
+    DevBuf cut_rows;           // int32[n_split_rows] (path-row indices)
+    // Partial rows of the groups, per width F: float[n_groups][2][F].  Slot 0 of a group holds the
+    // sum of the tail of a row that began in an earlier group, slot 1 the sum of the row still
+    // open at the group's end.  Written by every launch before it is read; sized at schedule time
+    // so that a launch never allocates.
+    struct Pieces { int F; DevBuf buf; };
+    std::vector<Pieces*> pieces;
+    ~Schedule() { for (Pieces* q : pieces) delete q; }
+    float* pieces_for(int F) const {
+        for (const Pieces* q : pieces)
+            if (q->F == F) return q->buf.as<float>();
+        return nullptr;
+    }
+    int ensure_pieces(int F) {
+        if (pieces_for(F) || n_split_rows == 0) return EPP_OK;
+        Pieces* q = new Pieces();
+        q->F = F;
+        if (q->buf.alloc((size_t)n_groups * 2 * (size_t)F * sizeof(float)) != EPP_OK) { delete q; return EPP_ERR_ALLOC; }
+        pieces.push_back(q);
+        return EPP_OK;
+    }
+    size_t bytes() const {
+        size_t b = group_row.bytes + cut_rows.bytes;
+        for (const Pieces* q : pieces) b += q->buf.bytes;
+        return b;
+    }
 };
 
 struct epp_path {

@@ -236,4 +236,4 @@ def test_backward_epoch_in_a_hip_graph():
         torch.cuda.synchronize()
         for l in range(L):
             assert torch.equal(Wgs[l], eager_w[l]), f"replay {rep} W' l={l}"
-        assert torch.allclose(Gs[0], eager_g0, rtol=1e-6, atol=1e-7)  # atomics on cut rows may reorder sums
+        assert torch.equal(Gs[0], eager_g0), f"replay {rep} gradient"

@@ -165,22 +165,28 @@ def test_error_paths():
         epp.epp_backward_aggregate(paths.path(0), x, x)  # aliasing
 
 
-def test_run_to_run_determinism_of_unsplit_rows():
+def test_run_to_run_determinism_of_every_row():
+    """Rows cut by group boundaries are summed from per-group pieces in a fixed order (no
+    floating-point atomics), so repeated launches agree bit for bit, cut rows included, and
+    whatever grad_out held before."""
     g = graphgen.random_graph("rmat", 20_000, seed=61, raw_draws=300_000)
     train = graphgen.training_set(g.n, 2000, 62)
     sets_o, paths_o = oprep(g, train, 2)
     paths = gpu_prepare(g, train, 2)
-    F = 32
-    X = graphgen.normal_rows(g.n, F, sets_o[1], 63)
+    X32 = graphgen.normal_rows(g.n, 32, sets_o[1], 63)
     p = paths.path(0)
-    p.set_group_size(F, 64)
-    a, b, c = (run_partial(p, X) for _ in range(3))
     ptr = paths_o[0].rowptr.astype(np.int64)
-    unsplit = paths_o[0].row_ids[(ptr[1:] - 1) // 64 == ptr[:-1] // 64]  # rows no group boundary cuts
-    assert np.array_equal(a[unsplit], b[unsplit]) and np.array_equal(a[unsplit], c[unsplit])
-    want = oracle.path_aggregate(g.n, paths_o[0], X)
-    for r in (a, b, c):
-        assert_close(r, want, "split rows")
+    for F, gs in ((32, 64), (32, 8), (7, 16)):  # long rows span many groups at gs = 8
+        X = np.ascontiguousarray(X32[:, :F])
+        p.set_group_size(F, gs)
+        cut = (ptr[1:] - 1) // gs != ptr[:-1] // gs
+        assert cut.sum() > 100 and p.info().n_split_rows == cut.sum()
+        a = run_partial(p, X)
+        b = run_partial(p, X, poison=float("nan"))
+        c = run_partial(p, X, poison=3.0)
+        rows = paths_o[0].row_ids
+        assert np.array_equal(a[rows], b[rows]) and np.array_equal(a[rows], c[rows]), (F, gs)
+        assert_close(a, oracle.path_aggregate(g.n, paths_o[0], X), f"F={F} gs={gs}")
 
 
 @pytest.mark.parametrize("k", [1, 2])
