@@ -161,9 +161,10 @@ __global__ __launch_bounds__(kBlock) void k_combine_cut_rows(const int32_t* __re
 // order), so no workgroup barrier is involved.
 //
 // The membership tests of the if-else variant cost a few registers, enough to lose a
-// wavefront per SIMD; its register budget is capped to the occupancy of the plain kernel.
+// wavefront per SIMD; its register budget is capped to the occupancy of the plain kernel
+// (five wavefronts per SIMD, four where the hot/cold branch of 8- and 16-byte lanes needs more).
 template <int VEC, int LOG2T, int U_, bool IFELSE, bool COLD>
-__global__ __launch_bounds__(kBlock, IFELSE ? (COLD ? 4 : 5) : 1) void k_aggregate(AggArgs a) {
+__global__ __launch_bounds__(kBlock, IFELSE ? ((COLD && VEC != 1) ? 4 : 5) : 4) void k_aggregate(AggArgs a) {
     constexpr int T = 1 << LOG2T;
     constexpr int S = 4 * T;              // pairs staged per slot
     constexpr int U = U_ < S ? U_ : S;    // S is a multiple of U
