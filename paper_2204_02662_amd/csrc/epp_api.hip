@@ -104,6 +104,7 @@ extern "C" int epp_path_set_group_size(epp_path_t* p, int F, int gs, epp_stream_
     if (F < 1) { epp_set_error("F must be >= 1"); return EPP_ERR_INVALID_ARG; }
     epp_path::WidthCfg* w = width_cfg(p, F);
     w->forced_gs = gs > 0 ? gs : 0;
+    if (w->sched) w->sched->drop_pieces(F);  // a table shared with other widths keeps theirs
     w->sched = nullptr;
     // drop cached tables that no width refers to any more
     for (size_t i = 0; i < p->scheds.size();) {

@@ -115,6 +115,10 @@ struct Schedule {
         pieces.push_back(q);
         return EPP_OK;
     }
+    void drop_pieces(int F) {  // hipFree waits for the device, so no launch can still be using them
+        for (size_t i = 0; i < pieces.size(); ++i)
+            if (pieces[i]->F == F) { delete pieces[i]; pieces.erase(pieces.begin() + i); return; }
+    }
     size_t bytes() const {
         size_t b = group_row.bytes + cut_rows.bytes;
         for (const Pieces* q : pieces) b += q->buf.bytes;
