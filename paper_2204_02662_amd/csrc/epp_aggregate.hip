@@ -451,16 +451,31 @@ __global__ __launch_bounds__(kBlock) void k_hot_bitmap(const int* __restrict__ c
     if ((threadIdx.x & 63) == 0 && (v >> 6) < ((n + 63) >> 6)) bits[v >> 6] = b;
 }
 
-// Set or clear the cold flag of every entry (hot == NULL: clear all).
+// Set or clear the cold flag of every entry (hot == NULL: clear all).  Two entries per lane:
+// 16-byte accesses, and the two bitmap lookups of a lane are in flight together.
+typedef int int4v __attribute__((ext_vector_type(4)));
 __global__ __launch_bounds__(kBlock) void k_mark_cold(int2v* __restrict__ cv, int64_t nnz,
                                                       const unsigned int* __restrict__ hot) {
-    int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int64_t e = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 2;
     if (e >= nnz) return;
-    int2v x = cv[e];
-    x.x &= ~kCold;
-    const int c = x.x & kColMask;
-    if (hot && !((hot[c >> 5] >> (c & 31)) & 1u)) x.x |= kCold;
-    cv[e] = x;  // whole pairs: full-line writes
+    if (e + 1 < nnz) {
+        int4v x = *reinterpret_cast<const int4v*>(cv + e);  // the entry array is 16-byte aligned, e is even
+        const int c0 = x.x & kColMask, c1 = x.z & kColMask;
+        x.x &= ~kCold;
+        x.z &= ~kCold;
+        if (hot) {
+            const unsigned int w0 = hot[c0 >> 5], w1 = hot[c1 >> 5];
+            if (!((w0 >> (c0 & 31)) & 1u)) x.x |= kCold;
+            if (!((w1 >> (c1 & 31)) & 1u)) x.z |= kCold;
+        }
+        *reinterpret_cast<int4v*>(cv + e) = x;
+    } else {
+        int2v x = cv[e];
+        x.x &= ~kCold;
+        const int c = x.x & kColMask;
+        if (hot && !((hot[c >> 5] >> (c & 31)) & 1u)) x.x |= kCold;
+        cv[e] = x;
+    }
 }
 
 }  // namespace
@@ -647,7 +662,7 @@ int epp_tune_locality(epp_path* p, int F, hipStream_t s, int* log2_slices) {
         hipLaunchKernelGGL(k_hot_bitmap, dim3((unsigned)((p->n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
                            cnt.as<int>(), p->n, thr, hot.as<unsigned long long>());
     }
-    hipLaunchKernelGGL(k_mark_cold, dim3((unsigned)((p->nnz + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
+    hipLaunchKernelGGL(k_mark_cold, dim3((unsigned)((p->nnz + 2 * kBlock - 1) / (2 * kBlock))), dim3(kBlock), 0, s,
                        reinterpret_cast<int2v*>(p->cv.p), p->nnz, thr > 0 ? hot.as<unsigned int>() : (const unsigned int*)nullptr);
     EPP_HIP_TRY(hipGetLastError());
     EPP_HIP_TRY(hipStreamSynchronize(s));

@@ -68,10 +68,16 @@ __global__ __launch_bounds__(kBlock) void k_mark_training(const int32_t* __restr
 }
 
 // keep-mask of every 64-edge segment and kept entries per tile.
+//
+// `mask` may still hold the keep-mask of the previous level (have_prev).  If N^{k-1} is a
+// subset of N^k (*not_subset == 0; always the case when every vertex has a self-loop), an entry
+// kept at the previous level has its column in N^{k-1}, hence in N^k, and is kept again: only
+// the other entries are loaded and looked up.  Once the sets are close to saturation this
+// turns a pass bound by the rate of random bitmap lookups into a scan of the previous mask.
 __global__ __launch_bounds__(kBlock) void k_edge_mask(const int32_t* __restrict__ col, int64_t nnz, int64_t n_seg,
-                                                      const unsigned int* __restrict__ bitmap32,
-                                                      unsigned long long* __restrict__ mask,
-                                                      int* __restrict__ tile_count) {
+                                                      const unsigned int* __restrict__ bitmap32, int have_prev,
+                                                      const int* __restrict__ not_subset,
+                                                      unsigned long long* mask, int* __restrict__ tile_count) {
     __shared__ int wave_cnt[4];
     const int wave = threadIdx.x >> 6, lane = lane_id();
     int cnt = 0;
@@ -79,18 +85,25 @@ __global__ __launch_bounds__(kBlock) void k_edge_mask(const int32_t* __restrict_
     // issued back to back so that the two dependent memory latencies are paid once per tile
     constexpr int kPerWave = kSegsPerTile / 4;
     const int64_t seg0 = (int64_t)blockIdx.x * kSegsPerTile + wave * kPerWave;
+    const bool use_prev = have_prev && *not_subset == 0;
+    bool known[kPerWave];
     int32_t c[kPerWave];
     unsigned int w[kPerWave];
 #pragma unroll
     for (int i = 0; i < kPerWave; ++i) {
+        const unsigned long long pm = (use_prev && seg0 + i < n_seg) ? mask[seg0 + i] : 0ull;
+        known[i] = (pm >> lane) & 1ull;
+    }
+#pragma unroll
+    for (int i = 0; i < kPerWave; ++i) {
         const int64_t e = (seg0 + i) * 64 + lane;
-        c[i] = e < nnz ? col[e] : -1;
+        c[i] = (e < nnz && !known[i]) ? col[e] : -1;
     }
 #pragma unroll
     for (int i = 0; i < kPerWave; ++i) w[i] = c[i] >= 0 ? bitmap32[c[i] >> 5] : 0u;
 #pragma unroll
     for (int i = 0; i < kPerWave; ++i) {
-        const bool keep = c[i] >= 0 && ((w[i] >> (c[i] & 31)) & 1u);
+        const bool keep = known[i] || (c[i] >= 0 && ((w[i] >> (c[i] & 31)) & 1u));
         const unsigned long long m = __ballot(keep);
         if (lane == 0 && seg0 + i < n_seg) mask[seg0 + i] = m;
         cnt += __popcll(m);
@@ -311,6 +324,14 @@ __global__ __launch_bounds__(kBlock) void k_bitmap_differs(const unsigned long l
     if (w < n_words && a[w] != b[w]) atomicOr(flag, 1);
 }
 
+// flag |= 1 if some member of set a is not in set b.
+__global__ __launch_bounds__(kBlock) void k_bitmap_not_subset(const unsigned long long* __restrict__ a,
+                                                              const unsigned long long* __restrict__ b, int64_t n_words,
+                                                              int* __restrict__ flag) {
+    int64_t w = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (w < n_words && (a[w] & ~b[w]) != 0ull) atomicOr(flag, 1);
+}
+
 inline unsigned grid_for(int64_t n, int per_block) { return (unsigned)((n + per_block - 1) / per_block); }
 
 // Pinned host staging for the few scalars read back per level.
@@ -454,13 +475,13 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
     }
 
     // all temporaries of the construction come from one allocation
-    DevBuf mask, seg_base, tile_cnt, tile_base, newptr, dev_total, err, stats;
+    DevBuf mask, seg_base, tile_cnt, tile_base, newptr, dev_total, err, not_subset, stats;
     const size_t max_tiles = std::max<size_t>(std::max(edge_tiles, word_tiles), 1);
     const size_t stats_bytes = (EPP_NCLASS + 1) * sizeof(unsigned long long);
     DevArena arena;
     EPP_TRY(arena.reserve(DevArena::rounded((size_t)n_seg * 8) + DevArena::rounded((size_t)n_seg * 4) +
                           2 * DevArena::rounded(max_tiles * 4) + DevArena::rounded((size_t)(n + 1) * 4) +
-                          2 * DevArena::rounded(8) + DevArena::rounded(stats_bytes)));
+                          3 * DevArena::rounded(8) + DevArena::rounded(stats_bytes)));
     arena.take(&mask, (size_t)n_seg * 8);
     arena.take(&seg_base, (size_t)n_seg * 4);
     arena.take(&tile_cnt, max_tiles * 4);
@@ -468,6 +489,7 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
     arena.take(&newptr, (size_t)(n + 1) * 4);
     arena.take(&dev_total, sizeof(long long));
     arena.take(&err, sizeof(int));
+    arena.take(&not_subset, sizeof(int));
     arena.take(&stats, stats_bytes);
     EPP_HIP_TRY(hipMemsetAsync(err.p, 0, sizeof(int), s));
     EPP_HIP_TRY(hipMemsetAsync(newptr.p, 0, newptr.bytes, s));
@@ -496,8 +518,16 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
         p->n_src = P->set_size[k];
         long long kept = 0;
         if (edge_tiles) {
+            // from the second level on the mask of the level before is reused where N^{k-1} lies in N^k
+            if (k > 0) {
+                EPP_HIP_TRY(hipMemsetAsync(not_subset.p, 0, sizeof(int), s));
+                hipLaunchKernelGGL(k_bitmap_not_subset, dim3(grid_for(n_words, kBlock)), dim3(kBlock), 0, s,
+                                   P->bitmaps[k - 1].as<unsigned long long>(), P->bitmaps[k].as<unsigned long long>(),
+                                   n_words, not_subset.as<int>());
+            }
             hipLaunchKernelGGL(k_edge_mask, dim3(edge_tiles), dim3(kBlock), 0, s, g->col, nnz, n_seg,
-                               P->bitmaps[k].as<unsigned int>(), mask.as<unsigned long long>(), tile_cnt.as<int>());
+                               P->bitmaps[k].as<unsigned int>(), k > 0 ? 1 : 0, not_subset.as<int>(),
+                               mask.as<unsigned long long>(), tile_cnt.as<int>());
             hipLaunchKernelGGL(k_scan_counts, dim3(1), dim3(1024), 0, s, tile_cnt.as<int>(), tile_base.as<int>(),
                                (int64_t)edge_tiles, dev_total.as<long long>());
             EPP_HIP_TRY(hipGetLastError());

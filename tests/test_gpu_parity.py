@@ -85,6 +85,27 @@ def test_small_random_graphs(seed):
     check_layers(g, train, 3, [int(x) for x in rng.integers(1, 70, 3)], 50 + seed, gs_list=(0, 1, 3))
 
 
+@pytest.mark.parametrize("loops,sym", [(True, True), (False, True), (False, False), (True, False)])
+def test_deep_paths_over_many_tiles(loops, sym):
+    """Four levels over a few hundred edge tiles.  With self-loops N^k grows monotonically and
+    every level after the first starts from the keep-mask of the level before; without them
+    the sets are not nested and every level tests all entries again.  Same paths either way."""
+    rng = np.random.default_rng(7 + 2 * loops + sym)
+    n = 60_000
+    edges = rng.integers(0, n, (250_000, 2))
+    edges = edges[edges[:, 0] != edges[:, 1]]
+    g = graphgen.csr_from_edges(n, [tuple(e) for e in edges.tolist()], self_loops=loops, symmetric=sym, normalise=sym)
+    train = rng.choice(n, size=40, replace=False)
+    L = 4
+    sets_o, paths_o = oprep(g, train, L)
+    nested = all(np.all(sets_o[k + 1][sets_o[k] != 0] != 0) for k in range(L))
+    assert nested == loops
+    sizes = [int((s != 0).sum()) for s in sets_o]
+    assert sizes[0] < sizes[1] < sizes[2] < sizes[3]  # the frontier is still growing at every level
+    paths = gpu_prepare(g, train, L)
+    assert_paths_bit_exact(paths, sets_o, paths_o, L)
+
+
 @pytest.mark.parametrize("F", [1, 2, 3, 4, 5, 6, 7, 8, 16, 31, 32, 41, 47, 64, 100, 128, 130, 256, 259, 300, 301])
 def test_widths_on_skewed_graph(F):
     """Several tiles, hubs that get split, a ragged tail, every vector shape."""
