@@ -113,31 +113,65 @@ __global__ __launch_bounds__(kBlock) void k_edge_mask(const int32_t* __restrict_
     if (threadIdx.x == 0) tile_count[blockIdx.x] = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
 }
 
-// Single-workgroup exclusive scan of `n` counts (n is at most a few hundred thousand).
+// Exclusive scan of `n` counts (per-tile numbers of kept entries or set bits).  A workgroup of
+// 1024 threads, kScanPerThread consecutive counts each, scans a chunk of kScanChunk counts;
+// k_scan_counts walks all chunks in one workgroup (short arrays), the three-kernel form scans
+// the chunks in parallel, then the chunk sums, then adds the chunk offsets.
+constexpr int kScanPerThread = 8;
+constexpr int kScanChunk = 1024 * kScanPerThread;
+
+// Scans in[base .. base + kScanChunk) into out, starting from `carry`; returns the chunk's sum
+// to every thread.  Called by all 1024 threads of the workgroup.
+__device__ __forceinline__ int scan_chunk(const int* __restrict__ in, int* __restrict__ out, int64_t n, int64_t base,
+                                          int carry) {
+    __shared__ int wave_sum[16];
+    const int wave = threadIdx.x >> 6, lane = lane_id();
+    const int64_t i0 = base + (int64_t)threadIdx.x * kScanPerThread;
+    int x[kScanPerThread];
+    int mine = 0;
+#pragma unroll
+    for (int j = 0; j < kScanPerThread; ++j) {
+        x[j] = i0 + j < n ? in[i0 + j] : 0;
+        mine += x[j];
+    }
+    const int incl = wave_inclusive_scan(mine);
+    if (lane == 63) wave_sum[wave] = incl;
+    __syncthreads();
+    int off = carry, all = 0;
+    for (int w = 0; w < 16; ++w) {
+        if (w < wave) off += wave_sum[w];
+        all += wave_sum[w];
+    }
+    __syncthreads();  // wave_sum is reused by the next call
+    off += incl - mine;
+#pragma unroll
+    for (int j = 0; j < kScanPerThread; ++j) {
+        if (i0 + j < n) out[i0 + j] = off;
+        off += x[j];
+    }
+    return all;
+}
+
 __global__ __launch_bounds__(1024) void k_scan_counts(const int* __restrict__ in, int* __restrict__ out, int64_t n,
                                                       long long* __restrict__ total) {
-    __shared__ int wave_sum[16];
-    __shared__ int carry_s;
-    const int wave = threadIdx.x >> 6, lane = lane_id();
-    if (threadIdx.x == 0) carry_s = 0;
-    __syncthreads();
-    for (int64_t base = 0; base < n; base += 1024) {
-        int64_t i = base + threadIdx.x;
-        int x = i < n ? in[i] : 0;
-        int incl = wave_inclusive_scan(x);
-        if (lane == 63) wave_sum[wave] = incl;
-        __syncthreads();
-        int off = carry_s, all = 0;
-        for (int w = 0; w < 16; ++w) {
-            if (w < wave) off += wave_sum[w];
-            all += wave_sum[w];
-        }
-        if (i < n) out[i] = off + incl - x;
-        __syncthreads();
-        if (threadIdx.x == 0) carry_s += all;
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) *total = carry_s;
+    int carry = 0;
+    for (int64_t base = 0; base < n; base += kScanChunk) carry += scan_chunk(in, out, n, base, carry);
+    if (threadIdx.x == 0) *total = carry;
+}
+
+__global__ __launch_bounds__(1024) void k_scan_chunks(const int* __restrict__ in, int* __restrict__ out, int64_t n,
+                                                      int* __restrict__ chunk_sum) {
+    const int all = scan_chunk(in, out, n, (int64_t)blockIdx.x * kScanChunk, 0);
+    if (threadIdx.x == 0) chunk_sum[blockIdx.x] = all;
+}
+
+__global__ __launch_bounds__(1024) void k_scan_add_offsets(int* __restrict__ out, int64_t n,
+                                                           const int* __restrict__ chunk_base) {
+    const int off = chunk_base[blockIdx.x];
+    const int64_t i0 = (int64_t)blockIdx.x * kScanChunk + (int64_t)threadIdx.x * kScanPerThread;
+#pragma unroll
+    for (int j = 0; j < kScanPerThread; ++j)
+        if (i0 + j < n) out[i0 + j] += off;
 }
 
 // Stable compaction of the kept entries into interleaved (col, val) pairs; seg_base[s]
@@ -334,6 +368,21 @@ __global__ __launch_bounds__(kBlock) void k_bitmap_not_subset(const unsigned lon
 
 inline unsigned grid_for(int64_t n, int per_block) { return (unsigned)((n + per_block - 1) / per_block); }
 
+// out = exclusive scan of in[0 .. n), *total = sum.  `tmp` holds 2 * ceil(n / kScanChunk) ints.
+inline size_t scan_tmp_bytes(int64_t n) { return (size_t)(2 * ((n + kScanChunk - 1) / kScanChunk) + 2) * sizeof(int); }
+void scan_counts(const int* in, int* out, int64_t n, long long* total, int* tmp, hipStream_t s) {
+    const int64_t chunks = (n + kScanChunk - 1) / kScanChunk;
+    if (chunks <= 2) {
+        hipLaunchKernelGGL(k_scan_counts, dim3(1), dim3(1024), 0, s, in, out, n, total);
+        return;
+    }
+    int* chunk_sum = tmp;
+    int* chunk_base = tmp + chunks;
+    hipLaunchKernelGGL(k_scan_chunks, dim3((unsigned)chunks), dim3(1024), 0, s, in, out, n, chunk_sum);
+    hipLaunchKernelGGL(k_scan_counts, dim3(1), dim3(1024), 0, s, (const int*)chunk_sum, chunk_base, chunks, total);
+    hipLaunchKernelGGL(k_scan_add_offsets, dim3((unsigned)chunks), dim3(1024), 0, s, out, n, (const int*)chunk_base);
+}
+
 // Pinned host staging for the few scalars read back per level.
 struct HostScalars {
     long long* p = nullptr;
@@ -475,17 +524,19 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
     }
 
     // all temporaries of the construction come from one allocation
-    DevBuf mask, seg_base, tile_cnt, tile_base, newptr, dev_total, err, not_subset, stats;
+    DevBuf mask, seg_base, tile_cnt, tile_base, scan_tmp, newptr, dev_total, err, not_subset, stats;
     const size_t max_tiles = std::max<size_t>(std::max(edge_tiles, word_tiles), 1);
     const size_t stats_bytes = (EPP_NCLASS + 1) * sizeof(unsigned long long);
     DevArena arena;
     EPP_TRY(arena.reserve(DevArena::rounded((size_t)n_seg * 8) + DevArena::rounded((size_t)n_seg * 4) +
-                          2 * DevArena::rounded(max_tiles * 4) + DevArena::rounded((size_t)(n + 1) * 4) +
+                          2 * DevArena::rounded(max_tiles * 4) + DevArena::rounded(scan_tmp_bytes(edge_tiles)) +
+                          DevArena::rounded((size_t)(n + 1) * 4) +
                           3 * DevArena::rounded(8) + DevArena::rounded(stats_bytes)));
     arena.take(&mask, (size_t)n_seg * 8);
     arena.take(&seg_base, (size_t)n_seg * 4);
     arena.take(&tile_cnt, max_tiles * 4);
     arena.take(&tile_base, max_tiles * 4);
+    arena.take(&scan_tmp, scan_tmp_bytes(edge_tiles));
     arena.take(&newptr, (size_t)(n + 1) * 4);
     arena.take(&dev_total, sizeof(long long));
     arena.take(&err, sizeof(int));
@@ -528,8 +579,8 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
             hipLaunchKernelGGL(k_edge_mask, dim3(edge_tiles), dim3(kBlock), 0, s, g->col, nnz, n_seg,
                                P->bitmaps[k].as<unsigned int>(), k > 0 ? 1 : 0, not_subset.as<int>(),
                                mask.as<unsigned long long>(), tile_cnt.as<int>());
-            hipLaunchKernelGGL(k_scan_counts, dim3(1), dim3(1024), 0, s, tile_cnt.as<int>(), tile_base.as<int>(),
-                               (int64_t)edge_tiles, dev_total.as<long long>());
+            scan_counts(tile_cnt.as<int>(), tile_base.as<int>(), (int64_t)edge_tiles, dev_total.as<long long>(),
+                        scan_tmp.as<int>(), s);
             EPP_HIP_TRY(hipGetLastError());
             EPP_HIP_TRY(hipMemcpyAsync(hs.p, dev_total.p, sizeof(long long), hipMemcpyDeviceToHost, s));
             EPP_HIP_TRY(hipStreamSynchronize(s));
