@@ -210,6 +210,32 @@ def test_run_to_run_determinism_of_every_row():
         assert_close(a, oracle.path_aggregate(g.n, paths_o[0], X), f"F={F} gs={gs}")
 
 
+def test_forward_aggregation_and_its_adjoint():
+    """Alg. 1's forward aggregation on the all-active kernel (the library is handed the forward
+    operator A), and the backward one on its transpose: each against the oracle, and
+    <A X, G> = <X, A^T G> across the two GPU results.  A is directed and randomly weighted."""
+    rng = np.random.default_rng(91)
+    n, F = 6000, 24
+    pairs = rng.integers(0, n, (60_000, 2))
+    pairs = pairs[pairs[:, 0] != pairs[:, 1]]
+    fwd = graphgen.csr_from_edges(n, [tuple(e) for e in pairs.tolist()], self_loops=True, symmetric=False,
+                                  normalise=False)
+    fwd.val[:] = rng.uniform(0.1, 1.0, fwd.nnz).astype(np.float32)
+    # transpose on the host with plain index arithmetic: entry (v <- u, w) becomes (u <- v, w)
+    dst = np.repeat(np.arange(n, dtype=np.int64), np.diff(fwd.rowptr))
+    order = np.lexsort((dst, fwd.col))
+    bwd = graphgen.Graph(n, np.concatenate([[0], np.cumsum(np.bincount(fwd.col, minlength=n))]).astype(np.int32),
+                         dst[order].astype(np.int32), fwd.val[order].copy())
+    X = graphgen.normal_rows(n, F, None, 92)
+    G = graphgen.normal_rows(n, F, None, 93)
+    AX = run_full(gpu_prepare_full(fwd), X)
+    AtG = run_full(gpu_prepare_full(bwd), G)
+    assert_close(AX, oracle.full_aggregate(n, fwd.rowptr, fwd.col, fwd.val, X), "forward")
+    assert_close(AtG, oracle.full_aggregate(n, bwd.rowptr, bwd.col, bwd.val, G), "backward")
+    lhs = float(np.sum(AX.astype(np.float64) * G)), float(np.sum(X.astype(np.float64) * AtG))
+    assert abs(lhs[0] - lhs[1]) <= 1e-5 * max(abs(lhs[0]), 1.0), lhs
+
+
 @pytest.mark.parametrize("k", [1, 2])
 def test_small_configs_every_entry(k):
     cfg = graphgen.make_config(k)
