@@ -172,6 +172,28 @@ def combine_study(args):
         del Y, W, G, Wg, Yg, ws
 
 
+def shape_study(args):
+    """The two combination kernels on `--rows` contiguous rows (k = -1: every vertex, no id
+    list) of width `--F` x `--Fo`: the plain matrix-core shape, for counter runs."""
+    import torch
+
+    import paper_2204_02662_amd as epp
+
+    dev = torch.device("cuda", 0)
+    n, Fi, Fo = args.rows, args.F, args.Fo
+    rowptr = torch.zeros(n + 1, dtype=torch.int32, device=dev)
+    none_i, none_f = torch.zeros(0, dtype=torch.int32, device=dev), torch.zeros(0, device=dev)
+    paths = epp.epp_prepare(n, rowptr, none_i, none_f, torch.zeros(1, dtype=torch.int32, device=dev), 1)
+    Y, G, W = (torch.randn(a, b, device=dev) for a, b in ((n, Fi), (n, Fo), (Fi, Fo)))
+    Wg, Yg = torch.empty(Fi, Fo, device=dev), torch.empty(n, Fi, device=dev)
+    ws = torch.empty(epp.epp_weight_gradient_workspace(paths, -1, Fi, Fo), dtype=torch.uint8, device=dev)
+    w_ms = _time_ms(lambda: epp.epp_weight_gradient(paths, -1, Y, G, Wg, ws))
+    y_ms = _time_ms(lambda: epp.epp_input_gradient(paths, -1, G, W, Yg))
+    fl = 2.0 * n * Fi * Fo
+    print(json.dumps({"study": "shape", "rows": n, "F_in": Fi, "F_out": Fo, "weight_grad_ms": w_ms, "input_grad_ms": y_ms,
+                      "weight_grad_TFLOPs": fl / w_ms / 1e9, "input_grad_TFLOPs": fl / y_ms / 1e9}), flush=True)
+
+
 def overlap_study(args):
     """On-the-fly preparation (the paper's last experiment): epp_prepare on a second stream while
     the first forward pass (all-active aggregations of every layer, this build's own kernel) runs
@@ -310,9 +332,11 @@ def gsfit_study(args):
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("study", choices=["gs", "depth", "combine", "gsfit", "overlap"])
+    ap.add_argument("study", choices=["gs", "depth", "combine", "gsfit", "overlap", "shape"])
     ap.add_argument("--config", type=int, default=4)
     ap.add_argument("--F", type=int, default=64)
+    ap.add_argument("--Fo", type=int, default=128)
+    ap.add_argument("--rows", type=int, default=4_600_000)
     ap.add_argument("--Ls", type=str, default="2,3,4,5,6")
     ap.add_argument("--log2n", type=lambda v: [int(x) for x in v.split(",")], default=[13, 15, 17, 19])
     ap.add_argument("--widths", type=lambda v: [int(x) for x in v.split(",")], default=[16, 64, 128])
@@ -322,7 +346,7 @@ def main():
     assert torch.cuda.is_available(), "the studies need a GPU"
     torch.cuda.set_device(0)
     {"gs": gs_study, "depth": depth_study, "combine": combine_study, "gsfit": gsfit_study,
-     "overlap": overlap_study}[args.study](args)
+     "overlap": overlap_study, "shape": shape_study}[args.study](args)
 
 
 if __name__ == "__main__":
