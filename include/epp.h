@@ -125,7 +125,8 @@ int epp_path_set_group_size(epp_path_t* p, int F, int gs, epp_stream_t stream);
  * handle (2 * n_groups * F floats per width, allocated at the first call with that width), in
  * group order and without floating-point atomics: equal inputs give bit-identical results.
  * Asynchronous on `stream` except for the first call with a new (path, F), which builds the
- * group schedule and synchronises once. */
+ * group schedule, allocates and synchronises once (so it must be made outside stream capture);
+ * every later call with that (path, F) only enqueues kernels and may be captured in a HIP graph. */
 int epp_backward_aggregate(epp_path_t* p, const float* grad_in, float* grad_out, int F, epp_stream_t stream);
 
 /* All-active backward aggregation (Alg. 1) over a handle from epp_prepare_full: writes
