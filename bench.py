@@ -196,8 +196,9 @@ def main():
                 ev[s][i][1].record()
         torch.cuda.synchronize()
         wall_ms = (time.perf_counter() - t) * 1e3 / steps
-        per_layer = {l: float(np.mean([ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(steps)]))
-                     for i, l in enumerate(order)}
+        samples = {l: [ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(steps)] for i, l in enumerate(order)}
+        per_layer = {l: float(np.mean(v)) for l, v in samples.items()}
+        timed.spread = {l: (float(np.median(v)), float(np.min(v))) for l, v in samples.items()}
         return wall_ms, per_layer
 
     # the first call per (path, width) also builds the group table and the locality marks
@@ -210,6 +211,7 @@ def main():
 
     ms_partial, layer_ms = timed(lambda l: epp.epp_backward_aggregate(path_objs[l], grad_in[l], grad_out[l]),
                                  args.steps, args.warmup)
+    layer_spread = timed.spread
     for l in range(L):
         infos.append(path_objs[l].info())
 
@@ -221,7 +223,7 @@ def main():
         layers.append({
             "l": l, "F": F, "rows": i.n_rows, "sources": i.n_src, "nnz": i.nnz, "max_len": i.max_len,
             "group_size": i.group_size, "groups": i.n_groups, "split_rows": i.n_split_rows,
-            "ms": ms, "algorithmic_bytes": bmin, "roofline_GBs": bmin / ms / 1e6 if ms > 0 else None,
+            "ms": ms, "ms_median": layer_spread[l][0], "ms_min": layer_spread[l][1], "algorithmic_bytes": bmin, "roofline_GBs": bmin / ms / 1e6 if ms > 0 else None,
             "roofline_frac": bmin / ms / 1e6 / HBM_PEAK_GBS if ms > 0 else None,
             "gather_GBs": bedge / ms / 1e6 if ms > 0 else None,
         })
