@@ -7,6 +7,12 @@
  * function aborts or throws across this boundary.  A handle (epp_paths_t / epp_path_t) must
  * not be used by two calls at the same time (calls on one stream, one after the other, are fine).
  *
+ * Environment variables read when a schedule is built (measurement knobs; defaults in brackets):
+ *   EPP_TUNE_GS           group size for every (path, F) that has none forced            [selector]
+ *   EPP_TUNE_HOT_MB       budget of the hot source rows, 0 switches hot/cold marking off [96]
+ *   EPP_TUNE_LOG2_SLICES  log2 of the XCD feature slices, 0..3                           [chosen per path]
+ * None of them changes a result beyond the order of floating-point additions.
+ *
  * Notation (paper, Table 1 / Sec. 3 / Sec. 4): V_t training set; N^k the k-neighbour set
  * of V_t (vertices reached from V_t by exactly k edges, N^0 = V_t); L layers; SG_l the
  * execution path of layer l with destination vertices N^{L-l} and, for each, the
