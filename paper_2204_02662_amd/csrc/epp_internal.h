@@ -136,6 +136,7 @@ struct epp_path {
     bool all_rows = false;       // all-active graph (handle from epp_prepare_full)
     // Streamed form: only rows with at least one entry, in ascending vertex order.
     int64_t n_stream_rows = 0;
+    DevBuf store;                // one allocation behind row_ids, rowptr and cv where they are views of it
     DevBuf row_ids;              // int32[n_stream_rows] vertex of each streamed row; unset: identity
     DevBuf rowptr;               // int32[n_stream_rows + 1]
     DevBuf cv;                   // int2[nnz]: (column id | cold flag bit 30 | row-end flag bit 31, weight bits)
@@ -171,7 +172,10 @@ struct epp_paths {
 
 // prepare.hip
 // histogram + max length of a built path; `stats_scratch`: (EPP_NCLASS + 1) * 8 device bytes, or NULL
-int epp_path_finish(epp_path* p, hipStream_t s, void* stats_scratch = nullptr);
+// `host_later` (pinned host memory, EPP_NCLASS + 1 words): the statistics are copied there
+// without waiting; the caller hands them to epp_path_set_stats after it has synchronised
+int epp_path_finish(epp_path* p, hipStream_t s, void* stats_scratch = nullptr, unsigned long long* host_later = nullptr);
+void epp_path_set_stats(epp_path* p, const unsigned long long* host);
 // ascending vertex ids of N^k (device, owned by `p`); the first call for k = 0 synchronises
 int epp_active_ids(epp_paths* p, int k, hipStream_t s, const int32_t** ids, int64_t* count);
 

@@ -174,32 +174,32 @@ __global__ __launch_bounds__(1024) void k_scan_add_offsets(int* __restrict__ out
         if (i0 + j < n) out[i0 + j] += off;
 }
 
-// Stable compaction of the kept entries into interleaved (col, val) pairs; seg_base[s]
-// receives the number of kept entries before segment s.
+// seg_base[s] = number of kept entries before segment s: the tile's offset plus the kept
+// entries of the tile's earlier segments.  One wavefront per tile.
+__global__ __launch_bounds__(64) void k_seg_base(const unsigned long long* __restrict__ mask, int64_t n_seg,
+                                                 const int* __restrict__ tile_base, int* __restrict__ seg_base) {
+    const int lane = lane_id();
+    const int64_t seg = (int64_t)blockIdx.x * kSegsPerTile + lane;
+    const int c = (lane < kSegsPerTile && seg < n_seg) ? __popcll(mask[seg]) : 0;
+    const int incl = wave_inclusive_scan(c);
+    if (lane < kSegsPerTile && seg < n_seg) seg_base[seg] = tile_base[blockIdx.x] + incl - c;
+}
+
+// Stable compaction of the kept entries into interleaved (col, val) pairs: a kept entry of
+// segment s goes to seg_base[s] + (kept entries before it in the segment).
 __global__ __launch_bounds__(kBlock) void k_edge_extract(const int32_t* __restrict__ col, const float* __restrict__ val,
                                                          int64_t n_seg, const unsigned long long* __restrict__ mask,
-                                                         const int* __restrict__ tile_base,
-                                                         int* __restrict__ seg_base, int2* __restrict__ cv) {
-    __shared__ int sbase[kSegsPerTile];
+                                                         const int* __restrict__ seg_base, int2* __restrict__ cv) {
     const int wave = threadIdx.x >> 6, lane = lane_id();
-    if (wave == 0) {
-        int64_t seg = (int64_t)blockIdx.x * kSegsPerTile + lane;
-        int c = (lane < kSegsPerTile && seg < n_seg) ? __popcll(mask[seg]) : 0;
-        int incl = wave_inclusive_scan(c);
-        if (lane < kSegsPerTile) {
-            int b = tile_base[blockIdx.x] + incl - c;
-            sbase[lane] = b;
-            if (seg < n_seg) seg_base[seg] = b;
-        }
-    }
-    __syncthreads();
     constexpr int kPerWave = kSegsPerTile / 4;
     unsigned long long m[kPerWave];
+    int sb[kPerWave];
     int2 x[kPerWave];
 #pragma unroll
     for (int i = 0; i < kPerWave; ++i) {
         const int64_t seg = (int64_t)blockIdx.x * kSegsPerTile + wave * kPerWave + i;
         m[i] = seg < n_seg ? mask[seg] : 0ull;
+        sb[i] = seg < n_seg ? seg_base[seg] : 0;
     }
 #pragma unroll
     for (int i = 0; i < kPerWave; ++i) {
@@ -208,22 +208,21 @@ __global__ __launch_bounds__(kBlock) void k_edge_extract(const int32_t* __restri
     }
 #pragma unroll
     for (int i = 0; i < kPerWave; ++i) {
-        if ((m[i] >> lane) & 1ull) {
-            const int pos = sbase[wave * kPerWave + i] + __popcll(m[i] & low_mask(lane));
-            cv[pos] = x[i];
-        }
+        if ((m[i] >> lane) & 1ull) cv[sb[i] + __popcll(m[i] & low_mask(lane))] = x[i];
     }
 }
 
 // Filtered row pointer of every vertex and membership of N^{k+1}.
 __global__ __launch_bounds__(kBlock) void k_row_flags(const int32_t* __restrict__ rowptr, int64_t n, int64_t nnz,
                                                       const unsigned long long* __restrict__ mask,
-                                                      const int* __restrict__ seg_base, int total,
+                                                      const int* __restrict__ seg_base,
+                                                      const long long* __restrict__ total_p,
                                                       int* __restrict__ newptr,
                                                       unsigned long long* __restrict__ bitmap_next) {
     int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     bool flag = false;
     if (v < n) {
+        const int total = (int)*total_p;  // kept entries of the level (the host has not read it yet)
         int64_t p0 = rowptr[v], p1 = rowptr[v + 1];
         int a = p0 >= nnz ? total : seg_base[p0 >> 6] + __popcll(mask[p0 >> 6] & low_mask((int)(p0 & 63)));
         int b = p1 >= nnz ? total : seg_base[p1 >> 6] + __popcll(mask[p1 >> 6] & low_mask((int)(p1 & 63)));
@@ -386,8 +385,8 @@ void scan_counts(const int* in, int* out, int64_t n, long long* total, int* tmp,
 // Pinned host staging for the few scalars read back per level.
 struct HostScalars {
     long long* p = nullptr;
-    int init() {
-        if (hipHostMalloc((void**)&p, 64 * sizeof(long long), hipHostMallocDefault) != hipSuccess) {
+    int init(size_t count = 64) {
+        if (hipHostMalloc((void**)&p, count * sizeof(long long), hipHostMallocDefault) != hipSuccess) {
             (void)hipGetLastError();
             epp_set_error("pinned host allocation failed");
             return EPP_ERR_ALLOC;
@@ -467,7 +466,14 @@ __global__ __launch_bounds__(kBlock) void k_check_cols(const int32_t* __restrict
 
 }  // namespace
 
-int epp_path_finish(epp_path* p, hipStream_t s, void* stats_scratch) {
+void epp_path_set_stats(epp_path* p, const unsigned long long* host) {
+    for (int c = 0; c < EPP_NCLASS; ++c) p->len_hist[c] = (int64_t)host[c];
+    int mx;
+    std::memcpy(&mx, &host[EPP_NCLASS], sizeof(int));
+    p->max_len = mx;
+}
+
+int epp_path_finish(epp_path* p, hipStream_t s, void* stats_scratch, unsigned long long* host_later) {
     DevBuf stats;
     if (stats_scratch) stats.view(stats_scratch, (EPP_NCLASS + 1) * sizeof(unsigned long long));
     else EPP_TRY(stats.alloc((EPP_NCLASS + 1) * sizeof(unsigned long long)));
@@ -480,13 +486,16 @@ int epp_path_finish(epp_path* p, hipStream_t s, void* stats_scratch) {
                            reinterpret_cast<int*>(stats.as<unsigned long long>() + EPP_NCLASS));
         EPP_HIP_TRY(hipGetLastError());
     }
-    unsigned long long host[EPP_NCLASS + 1];
-    EPP_HIP_TRY(hipMemcpyAsync(host, stats.p, sizeof(host), hipMemcpyDeviceToHost, s));
-    EPP_HIP_TRY(hipStreamSynchronize(s));
-    for (int c = 0; c < EPP_NCLASS; ++c) p->len_hist[c] = (int64_t)host[c];
-    int mx;
-    std::memcpy(&mx, &host[EPP_NCLASS], sizeof(int));
-    p->max_len = mx;
+    if (host_later) {
+        // pinned destination: the caller reads it (epp_path_set_stats) after its own synchronisation
+        EPP_HIP_TRY(hipMemcpyAsync(host_later, stats.p, (EPP_NCLASS + 1) * sizeof(unsigned long long),
+                                   hipMemcpyDeviceToHost, s));
+    } else {
+        unsigned long long host[EPP_NCLASS + 1];
+        EPP_HIP_TRY(hipMemcpyAsync(host, stats.p, sizeof(host), hipMemcpyDeviceToHost, s));
+        EPP_HIP_TRY(hipStreamSynchronize(s));
+        epp_path_set_stats(p, host);
+    }
     if (p->n_stream_rows > 0) {
         hipLaunchKernelGGL(k_mark_row_ends, dim3(grid_for(p->n_stream_rows, kBlock)), dim3(kBlock), 0, s,
                            p->rowptr.as<int32_t>(), p->n_stream_rows, p->cv.as<int2>());
@@ -509,8 +518,11 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
     const unsigned edge_tiles = grid_for(n_seg, kSegsPerTile);
     const unsigned word_tiles = grid_for(n_words, kWordsPerTile);
 
+    // pinned words read back from the device: [0] kept entries, [1] |N^{k+1}| (also the scratch of
+    // compact_bitmap), then EPP_NCLASS + 1 statistics words per level
+    constexpr int kStatWords = EPP_NCLASS + 1;
     HostScalars hs;
-    EPP_TRY(hs.init());
+    EPP_TRY(hs.init(8 + (size_t)L * kStatWords));
     epp_paths* P = new epp_paths();
     struct Guard { epp_paths* p; ~Guard() { delete p; } } guard{P};
     P->L = L;
@@ -526,19 +538,19 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
     // all temporaries of the construction come from one allocation
     DevBuf mask, seg_base, tile_cnt, tile_base, scan_tmp, newptr, dev_total, err, not_subset, stats;
     const size_t max_tiles = std::max<size_t>(std::max(edge_tiles, word_tiles), 1);
-    const size_t stats_bytes = (EPP_NCLASS + 1) * sizeof(unsigned long long);
+    const size_t stats_bytes = kStatWords * sizeof(unsigned long long);
     DevArena arena;
     EPP_TRY(arena.reserve(DevArena::rounded((size_t)n_seg * 8) + DevArena::rounded((size_t)n_seg * 4) +
                           2 * DevArena::rounded(max_tiles * 4) + DevArena::rounded(scan_tmp_bytes(edge_tiles)) +
                           DevArena::rounded((size_t)(n + 1) * 4) +
-                          3 * DevArena::rounded(8) + DevArena::rounded(stats_bytes)));
+                          3 * DevArena::rounded(16) + DevArena::rounded(stats_bytes)));
     arena.take(&mask, (size_t)n_seg * 8);
     arena.take(&seg_base, (size_t)n_seg * 4);
     arena.take(&tile_cnt, max_tiles * 4);
     arena.take(&tile_base, max_tiles * 4);
     arena.take(&scan_tmp, scan_tmp_bytes(edge_tiles));
     arena.take(&newptr, (size_t)(n + 1) * 4);
-    arena.take(&dev_total, sizeof(long long));
+    arena.take(&dev_total, 2 * sizeof(long long));  // [0] kept entries, [1] rows of the level
     arena.take(&err, sizeof(int));
     arena.take(&not_subset, sizeof(int));
     arena.take(&stats, stats_bytes);
@@ -561,13 +573,20 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
     EPP_TRY(compact_bitmap(P->bitmaps[0], n, nullptr, 0, nullptr, nullptr, &P->set_size[0], tile_cnt, tile_base,
                            dev_total, hs, s));
 
+    // One level: everything that only needs the two counts (kept entries, rows) on the device is
+    // enqueued first, the host waits once for both, makes one allocation for the path's three
+    // arrays, and enqueues the passes that fill them.  The row-length statistics come back
+    // through pinned memory and are read after the last level.
+    std::vector<epp_path*> built;  // in level order, for the statistics
     for (int k = 0; k < L; ++k) {
         const int l = L - 1 - k;  // rows N^{k+1} = N^{L-l}, sources N^k = N^{L-l-1}
         epp_path* p = new epp_path();
         P->path[l] = p;
+        built.push_back(p);
         p->n = n;
         p->n_src = P->set_size[k];
-        long long kept = 0;
+        long long* d_total = dev_total.as<long long>();
+        EPP_HIP_TRY(hipMemsetAsync(d_total, 0, 2 * sizeof(long long), s));
         if (edge_tiles) {
             // from the second level on the mask of the level before is reused where N^{k-1} lies in N^k
             if (k > 0) {
@@ -579,32 +598,50 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
             hipLaunchKernelGGL(k_edge_mask, dim3(edge_tiles), dim3(kBlock), 0, s, g->col, nnz, n_seg,
                                P->bitmaps[k].as<unsigned int>(), k > 0 ? 1 : 0, not_subset.as<int>(),
                                mask.as<unsigned long long>(), tile_cnt.as<int>());
-            scan_counts(tile_cnt.as<int>(), tile_base.as<int>(), (int64_t)edge_tiles, dev_total.as<long long>(),
-                        scan_tmp.as<int>(), s);
-            EPP_HIP_TRY(hipGetLastError());
-            EPP_HIP_TRY(hipMemcpyAsync(hs.p, dev_total.p, sizeof(long long), hipMemcpyDeviceToHost, s));
-            EPP_HIP_TRY(hipStreamSynchronize(s));
-            kept = hs.p[0];
-        }
-        p->nnz = kept;
-        EPP_TRY(p->cv.alloc((size_t)kept * sizeof(int2)));
-        if (edge_tiles) {
-            hipLaunchKernelGGL(k_edge_extract, dim3(edge_tiles), dim3(kBlock), 0, s, g->col, g->val, n_seg,
-                               mask.as<unsigned long long>(), tile_base.as<int>(), seg_base.as<int>(),
-                               p->cv.as<int2>());
+            scan_counts(tile_cnt.as<int>(), tile_base.as<int>(), (int64_t)edge_tiles, d_total, scan_tmp.as<int>(), s);
+            hipLaunchKernelGGL(k_seg_base, dim3(edge_tiles), dim3(64), 0, s, mask.as<unsigned long long>(), n_seg,
+                               tile_base.as<int>(), seg_base.as<int>());
             EPP_HIP_TRY(hipGetLastError());
         }
         if (n > 0) {
             hipLaunchKernelGGL(k_row_flags, dim3(grid_for(n, kBlock)), dim3(kBlock), 0, s, g->rowptr, n, nnz,
-                               mask.as<unsigned long long>(), seg_base.as<int>(), (int)kept, newptr.as<int>(),
-                               P->bitmaps[k + 1].as<unsigned long long>());
+                               mask.as<unsigned long long>(), seg_base.as<int>(), (const long long*)d_total,
+                               newptr.as<int>(), P->bitmaps[k + 1].as<unsigned long long>());
+            // rows of the level: set bits of the new bitmap, counted per tile of words and scanned
+            // (the edge-tile offsets are no longer needed: seg_base holds them)
+            hipLaunchKernelGGL(k_bitmap_count, dim3(word_tiles), dim3(kBlock), 0, s,
+                               P->bitmaps[k + 1].as<unsigned long long>(), n_words, tile_cnt.as<int>());
+            hipLaunchKernelGGL(k_scan_counts, dim3(1), dim3(1024), 0, s, tile_cnt.as<int>(), tile_base.as<int>(),
+                               (int64_t)word_tiles, d_total + 1);
             EPP_HIP_TRY(hipGetLastError());
         }
-        EPP_TRY(compact_bitmap(P->bitmaps[k + 1], n, newptr.as<int>(), (int)kept, &p->row_ids, &p->rowptr,
-                               &P->set_size[k + 1], tile_cnt, tile_base, dev_total, hs, s));
-        p->n_rows = P->set_size[k + 1];
-        p->n_stream_rows = p->n_rows;  // every row of a path has at least one entry
-        EPP_TRY(epp_path_finish(p, s, stats.p));
+        EPP_HIP_TRY(hipMemcpyAsync(hs.p, d_total, 2 * sizeof(long long), hipMemcpyDeviceToHost, s));
+        EPP_HIP_TRY(hipStreamSynchronize(s));
+        const long long kept = hs.p[0], R = hs.p[1];
+        p->nnz = kept;
+        p->n_rows = R;
+        p->n_stream_rows = R;  // every row of a path has at least one entry
+        P->set_size[k + 1] = R;
+        // entries | row ids | row pointer, each 256-byte aligned
+        const size_t cv_bytes = (size_t)kept * sizeof(int2), ids_bytes = (size_t)R * 4, ptr_bytes = (size_t)(R + 1) * 4;
+        EPP_TRY(p->store.alloc(DevArena::rounded(cv_bytes) + DevArena::rounded(ids_bytes) + DevArena::rounded(ptr_bytes)));
+        char* base = p->store.as<char>();
+        p->cv.view(base, cv_bytes);
+        p->row_ids.view(base + DevArena::rounded(cv_bytes), ids_bytes);
+        p->rowptr.view(base + DevArena::rounded(cv_bytes) + DevArena::rounded(ids_bytes), ptr_bytes);
+        if (edge_tiles) {
+            hipLaunchKernelGGL(k_edge_extract, dim3(edge_tiles), dim3(kBlock), 0, s, g->col, g->val, n_seg,
+                               mask.as<unsigned long long>(), seg_base.as<int>(), p->cv.as<int2>());
+        }
+        if (n > 0) {
+            hipLaunchKernelGGL(k_bitmap_compact, dim3(word_tiles), dim3(kBlock), 0, s,
+                               P->bitmaps[k + 1].as<unsigned long long>(), n_words, tile_base.as<int>(), newptr.as<int>(),
+                               p->row_ids.as<int32_t>(), p->rowptr.as<int32_t>(), (int64_t)R, (int)kept);
+        } else {
+            EPP_HIP_TRY(hipMemsetAsync(p->rowptr.p, 0, sizeof(int32_t), s));
+        }
+        EPP_HIP_TRY(hipGetLastError());
+        EPP_TRY(epp_path_finish(p, s, stats.p, reinterpret_cast<unsigned long long*>(hs.p) + 8 + (size_t)k * kStatWords));
         // Fixed point: N^{k+1} == N^k means every further set is the same set, so every deeper
         // layer (rows and sources both equal to it) has exactly this path; share it.
         if (k + 1 < L && P->set_size[k + 1] == P->set_size[k]) {
@@ -630,6 +667,8 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
         }
     }
     EPP_HIP_TRY(hipStreamSynchronize(s));
+    for (size_t k = 0; k < built.size(); ++k)
+        epp_path_set_stats(built[k], reinterpret_cast<const unsigned long long*>(hs.p) + 8 + k * kStatWords);
     guard.p = nullptr;
     *out = P;
     return EPP_OK;
