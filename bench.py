@@ -69,6 +69,7 @@ def cpu_baseline(cfg, budget_s: float):
     work = [paths_o[l].col.size * cfg.widths[l] for l in range(L)]
     total_work = float(sum(work))
     est_ms, sampled_s, strides = 0.0, 0.0, []
+    est1_ms, sampled1_s, strides1 = 0.0, 0.0, []
     for l in range(L - 1, -1, -1):
         po, F = paths_o[l], cfg.widths[l]
         X = graphgen.layer_gradient(cfg, l, sets_o[L - l - 1])
@@ -92,12 +93,29 @@ def cpu_baseline(cfg, budget_s: float):
         est_ms += dt / max(frac, 1e-12) * 1e3
         sampled_s += dt
         strides.append(stride)
+        # the same on one thread, on a sample thinned by the thread count (about the same wall time)
+        stride1 = stride * threads
+        if threads > 1 and R >= 64 * stride1:
+            oracle.set_threads(1)
+            t = time.perf_counter()
+            oracle.path_aggregate(g.n, po, X, first=0, stride=stride1)
+            dt1 = max(time.perf_counter() - t, 1e-4)
+            oracle.set_threads(threads)
+            est1_ms += dt1 / max(lens[0::stride1].sum() / max(po.col.size, 1), 1e-12) * 1e3
+            sampled1_s += dt1
+            strides1.append(stride1)
+        else:
+            est1_ms = float("nan")
         del X
-    return {
+    out = {
         "value": est_ms, "unit": "ms/epoch", "cores": threads, "kind": "oracle",
         "sample": (f"every k-th path row of each layer (k={strides} for l=L-1..0), all widths; "
                    f"{sampled_s:.1f} s of CPU work scaled by the share of entries sampled"),
     }
+    if est1_ms == est1_ms and strides1:  # not NaN: every layer was large enough to thin
+        out["one_thread"] = {"value": est1_ms, "unit": "ms/epoch", "cores": 1,
+                             "sample": f"every k-th path row (k={strides1}); {sampled1_s:.1f} s of CPU work, scaled"}
+    return out
 
 
 def main():
