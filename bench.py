@@ -165,6 +165,7 @@ def main():
     t_paths = epp.epp_prepare(tiny.n, t_rowptr, t_col, t_val, torch.arange(8, dtype=torch.int32, device=dev), L)
     for l in range(L):
         t_x = torch.zeros(tiny.n, cfg.widths[l], device=dev)
+        t_paths.path(l).prepare_width(cfg.widths[l])
         epp.epp_backward_aggregate(t_paths.path(l), t_x, torch.zeros_like(t_x))
     del t_paths, t_rowptr, t_col, t_val, t_x
     torch.cuda.synchronize()
@@ -219,13 +220,13 @@ def main():
         timed.spread = {l: (float(np.median(v)), float(np.min(v))) for l, v in samples.items()}
         return wall_ms, per_layer
 
-    # the first call per (path, width) also builds the group table and the locality marks
+    # one-off per (path, width): group table, partial rows, locality marks
     torch.cuda.synchronize()
     t = time.perf_counter()
     for l in order:
-        epp.epp_backward_aggregate(path_objs[l], grad_in[l], grad_out[l])
+        path_objs[l].prepare_width(cfg.widths[l])
     torch.cuda.synchronize()
-    first_epoch_ms = (time.perf_counter() - t) * 1e3
+    schedule_ms = (time.perf_counter() - t) * 1e3
 
     ms_partial, layer_ms = timed(lambda l: epp.epp_backward_aggregate(path_objs[l], grad_in[l], grad_out[l]),
                                  args.steps, args.warmup)
@@ -247,7 +248,7 @@ def main():
         })
     dom = max(layers, key=lambda d: d["ms"])
     traffic, l2_hit = read_traffic(cfg.name).get(dom["l"], (None, None))
-    # the machine's own random-row gather rate (tools/gather_rate.hip): 235 G lines/s from L2, 60 G lines/s beyond
+    # the machine's own random-row gather rate (profiles/gather_rate_microbenchmark.md): 235 G lines/s from L2, 60 G lines/s beyond
     lines = dom["nnz"] * ((dom["F"] * 4 + 127) // 128)
     model_ms = lines * ((1.0 - l2_hit) / 60e9 + l2_hit / 235e9) * 1e3 if l2_hit is not None else None
     roofline = {
@@ -274,7 +275,7 @@ def main():
         "roofline": roofline,
         "partially_active": {"ms_per_epoch": ms_partial, "sum_layer_ms": sum(layer_ms.values()), "layers": layers},
         "prepare_ms": prepare_ms,
-        "schedule_ms": max(first_epoch_ms - ms_partial, 0.0),  # one-off part of the first epoch
+        "schedule_ms": schedule_ms,  # one-off epp_path_prepare_width of every layer
         # one-off path construction: two passes over the column ids, one over the kept weights,
         # the (col, val) pairs written once, row pointer read and filtered pointer written per level
         # (layers past the fixed point of the active sets are built once)
@@ -286,6 +287,8 @@ def main():
     }
 
     if full is not None:
+        for l in order:
+            full.prepare_width(cfg.widths[l])
         k_full = max(3, args.steps // 4)
         ms_full, full_layer_ms = timed(lambda l: epp.epp_full_aggregate(full, grad_in[l], grad_out[l]), k_full,
                                        min(args.warmup, 2))

@@ -35,7 +35,28 @@ extern "C" {
 #define EPP_ERR_ALLOC (-4)           /* device or host allocation failed                    */
 #define EPP_ERR_HIP (-5)             /* a HIP runtime call failed (message has the detail)  */
 
-typedef void* epp_stream_t; /* a hipStream_t; NULL = the default stream */
+typedef void* epp_stream_t; /* a hipStream_t (spelled void* so that this header needs no HIP header);
+                               NULL = the default stream */
+
+/* Device-memory allocator of the caller (for instance PyTorch's caching allocator), so that the
+ * framework that owns the GPU's memory also owns every byte the library holds: the handle keeps a
+ * copy of the struct and takes every device buffer from it, the long-lived ones (path arrays,
+ * bitmaps of N^k, group tables, partial rows) and the temporaries of a call, and gives each back
+ * through `free` (at the latest when the handle is destroyed).
+ *   alloc   returns device memory of at least `bytes` bytes, 256-byte aligned, usable at once on the
+ *           stream of the call that asks for it; NULL = failure (the call returns EPP_ERR_ALLOC)
+ *   free    takes back a block from `alloc`.  It may be called while work that uses the block is
+ *           still queued on the stream of the library call that is freeing it: the allocator must
+ *           be stream-ordered on that stream (PyTorch's is, for the stream a block was allocated
+ *           on) or wait itself.  epp_destroy_paths / epp_destroy_path take no stream: finish the
+ *           work on a handle before destroying it.
+ *   ctx     passed through to both.
+ * A NULL epp_alloc_t pointer (or alloc == NULL) selects hipMalloc / hipFree. */
+typedef struct {
+    void* (*alloc)(size_t bytes, void* ctx);
+    void (*free)(void* p, void* ctx);
+    void* ctx;
+} epp_alloc_t;
 
 /* Input graph: pull-mode CSR of the BACKWARD operator M (Alg. 1, backward aggregation
  * loop: X'_v += e_vu * Y'_u for u in N(v)).  Row v lists the sources u with weight e_vu.
@@ -75,20 +96,24 @@ typedef struct {
  *   g          host struct with device arrays (read only during the call)
  *   train_ids  device, n_train entries; duplicates allowed (set semantics)
  *   L          number of layers, >= 1
+ *   alloc      the caller's device allocator, or NULL (see epp_alloc_t)
  *   stream     work is enqueued here; the call synchronises the stream before returning
  *   out        receives a handle owned by the library; release with epp_destroy_paths
- * n_train = 0 is valid (all paths empty).  Any id outside [0, n): EPP_ERR_OUT_OF_RANGE_ID. */
-int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t n_train, int L,
+ * n_train = 0 is valid (all paths empty).  Any training id or column id outside [0, n):
+ * EPP_ERR_OUT_OF_RANGE_ID; a row pointer that does not rise from 0 to nnz: EPP_ERR_INVALID_ARG
+ * (both are checked on the GPU as part of the first pass; neither can make a kernel fault). */
+int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t n_train, int L, const epp_alloc_t* alloc,
                 epp_stream_t stream, epp_paths_t** out);
 
 /* The all-active baseline (Alg. 1, backward aggregation over every vertex of the input
  * graph) wrapped as a "path" whose rows are all n vertices, so that the same kernels run
- * it.  Copies what it needs; g may be freed afterwards. */
-int epp_prepare_full(const epp_csr_t* g, epp_stream_t stream, epp_path_t** out);
+ * it.  Copies what it needs; g may be freed afterwards.  The arrays are checked as in epp_prepare. */
+int epp_prepare_full(const epp_csr_t* g, const epp_alloc_t* alloc, epp_stream_t stream, epp_path_t** out);
 
 int epp_num_layers(const epp_paths_t* p);
 /* Path of layer l in [0, L) as numbered in Alg. 2 (layer L-1 runs first in an epoch).
- * Borrowed pointer, valid until epp_destroy_paths.  NULL if l is out of range. */
+ * Borrowed pointer, valid until epp_destroy_paths.  NULL if l is out of range.  (The handle is
+ * not const: preparing a width and aggregating over the path change its schedules.) */
 epp_path_t* epp_get_path(epp_paths_t* p, int l);
 
 int epp_path_info(const epp_path_t* p, epp_path_info_t* info /* host */);
@@ -116,9 +141,20 @@ int epp_select_group_size(const epp_path_t* p, int F);
  * clamps to 1.  Pure host function. */
 int epp_paper_linreg_group_size(int64_t vertices, int64_t undirected_edges);
 
+/* One-off preparation of a path for gradient width F: builds the group table for the group size
+ * in force (the selector's, or the one forced by epp_path_set_group_size), allocates the
+ * partial rows of the groups (2 * n_groups * F floats, only if some row is cut by a group
+ * boundary) and chooses the cache-locality marks of the entries.  Allocates through the handle's
+ * allocator and synchronises `stream`; must not be called under stream capture.  Calling it again
+ * for a prepared width does nothing.  The aggregate entry points below require it: they never
+ * allocate and never wait. */
+int epp_path_prepare_width(epp_path_t* p, int F, epp_stream_t stream);
+
 /* Force the group size used for width F (sweeps, ablations); gs <= 0 restores the selector.
  * Rebuilds the group table: group g holds entries [g*gs, (g+1)*gs) of the edge array, so a
- * row longer than gs is always cut and short rows share a group.  Synchronises. */
+ * row longer than gs is always cut and short rows share a group.  Prepares the width as
+ * epp_path_prepare_width does (allocates, synchronises).  The partial rows of the previous
+ * table are freed: a HIP graph captured with the old table must not be replayed any more. */
 int epp_path_set_group_size(epp_path_t* p, int F, int gs, epp_stream_t stream);
 
 /* Partially-active backward aggregation of one layer (Alg. 2, aggregation loop):
@@ -128,15 +164,15 @@ int epp_path_set_group_size(epp_path_t* p, int F, int gs, epp_stream_t stream);
  *   rows of grad_out outside the path are NOT touched (zero them once; the active sets never
  *   change across epochs); rows of grad_in outside the source set are never read.
  * A row whose list is cut by group boundaries is summed from per-group partial rows kept in the
- * handle (2 * n_groups * F floats per width, allocated at the first call with that width), in
- * group order and without floating-point atomics: equal inputs give bit-identical results.
- * Asynchronous on `stream` except for the first call with a new (path, F), which builds the
- * group schedule, allocates and synchronises once (so it must be made outside stream capture);
- * every later call with that (path, F) only enqueues kernels and may be captured in a HIP graph. */
+ * handle, in group order and without floating-point atomics: equal inputs give bit-identical
+ * results.  The call only enqueues kernels on `stream`: no allocation, no host wait, so it may be
+ * captured in a HIP graph.  The width must have been prepared with epp_path_prepare_width
+ * (EPP_ERR_INVALID_ARG otherwise). */
 int epp_backward_aggregate(epp_path_t* p, const float* grad_in, float* grad_out, int F, epp_stream_t stream);
 
 /* All-active backward aggregation (Alg. 1) over a handle from epp_prepare_full: writes
- * every one of the n rows of grad_out (rows with empty lists become zero). */
+ * every one of the n rows of grad_out (rows with empty lists become zero).  Enqueues only; the
+ * width must have been prepared on `full`. */
 int epp_full_aggregate(epp_path_t* full, const float* grad_in, float* grad_out, int F, epp_stream_t stream);
 
 /* If-else selective scheduling (Sec. 4, the first straightforward alternative; comparison
@@ -145,7 +181,7 @@ int epp_full_aggregate(epp_path_t* full, const float* grad_in, float* grad_out, 
  * the membership bitmaps kept in `paths`.  Same result and output contract as
  * epp_backward_aggregate(epp_get_path(paths, l), ...): rows of N^{L-l} are overwritten, all
  * other rows untouched, inactive source rows are never read.  The whole edge array of the
- * graph is still traversed. */
+ * graph is still traversed.  Enqueues only; the width must have been prepared on `full`. */
 int epp_ifelse_aggregate(epp_path_t* full, const epp_paths_t* paths, int l, const float* grad_in, float* grad_out,
                          int F, epp_stream_t stream);
 
@@ -166,7 +202,7 @@ typedef struct {
     const float* val;       /* device, nnz                            */
 } epp_path_arrays_t;
 int epp_paths_import(int64_t n, int L, const int32_t* train_ids, int64_t n_train, const epp_path_arrays_t* layers,
-                     epp_stream_t stream, epp_paths_t** out);
+                     const epp_alloc_t* alloc, epp_stream_t stream, epp_paths_t** out);
 
 /* Combination stage of the backward pass restricted to the active rows (Alg. 1, backward
  * loop: W'(l) = Y(l)^T (x) X'(l+1) and Y'(l) = X'(l+1) (x) W(l)^T; by Theorem 1 the rows of
@@ -183,8 +219,8 @@ int epp_paths_import(int64_t n, int L, const int32_t* train_ids, int64_t n_train
  *   workspace  device scratch of at least epp_weight_gradient_workspace(...) bytes, 16-byte
  *            aligned, owned by the caller; holds partial sums over blocks of rows that a second
  *            kernel adds in a fixed order (results do not depend on timing)
- * 1 <= F_in, F_out <= 4096.  Asynchronous on `stream` (the first use of k = 0 builds the id
- * list of N^0 and synchronises once).  Matrices must not alias. */
+ * 1 <= F_in, F_out <= 4096.  Asynchronous on `stream`: both calls only enqueue kernels (no
+ * allocation, no host wait).  Matrices must not alias. */
 int64_t epp_weight_gradient_workspace(const epp_paths_t* paths, int k, int F_in, int F_out); /* bytes, < 0: error */
 int epp_weight_gradient(epp_paths_t* paths, int k, const float* Y, int F_in, const float* grad_X, int F_out,
                         float* grad_W, void* workspace, int64_t workspace_bytes, epp_stream_t stream);

@@ -28,6 +28,7 @@ EXPORTED = [
     "epp_backward_aggregate", "epp_full_aggregate", "epp_destroy_paths", "epp_destroy_path",
     "epp_last_error", "epp_paper_linreg_group_size", "epp_ifelse_aggregate",
     "epp_weight_gradient_workspace", "epp_weight_gradient", "epp_input_gradient", "epp_paths_import",
+    "epp_path_prepare_width",
 ]
 
 
@@ -45,6 +46,45 @@ class _Csr(ctypes.Structure):
 class _PathArrays(ctypes.Structure):
     _fields_ = [("n_rows", ctypes.c_int64), ("nnz", ctypes.c_int64), ("row_ids", ctypes.c_void_p),
                 ("rowptr", ctypes.c_void_p), ("col", ctypes.c_void_p), ("val", ctypes.c_void_p)]
+
+
+_ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p)
+_FREE_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)
+
+
+class _Alloc(ctypes.Structure):
+    _fields_ = [("alloc", _ALLOC_FN), ("free", _FREE_FN), ("ctx", ctypes.c_void_p)]
+
+
+#: calls and bytes that went through the PyTorch-backed allocator handed to the library
+alloc_stats = {"allocs": 0, "frees": 0, "bytes": 0, "live": 0}
+
+
+def _torch_alloc(nbytes, _ctx):
+    """epp_alloc_t.alloc: a block of PyTorch's caching allocator on the current device and stream."""
+    try:
+        ptr = torch.cuda.caching_allocator_alloc(int(nbytes))
+    except Exception:  # out of memory: the library reports EPP_ERR_ALLOC
+        return None
+    alloc_stats["allocs"] += 1
+    alloc_stats["bytes"] += int(nbytes)
+    alloc_stats["live"] += 1
+    return ptr
+
+
+def _torch_free(ptr, _ctx):
+    """epp_alloc_t.free: the block goes back to the caching allocator (stream-ordered reuse)."""
+    alloc_stats["frees"] += 1
+    alloc_stats["live"] -= 1
+    torch.cuda.caching_allocator_delete(ptr)
+
+
+_TORCH_ALLOC = _Alloc(_ALLOC_FN(_torch_alloc), _FREE_FN(_torch_free), None)
+
+
+def _allocator(use_torch: bool):
+    """Pointer to the PyTorch-backed epp_alloc_t, or NULL for the library's own hipMalloc."""
+    return ctypes.byref(_TORCH_ALLOC) if use_torch else None
 
 
 class _PathInfo(ctypes.Structure):
@@ -66,8 +106,10 @@ def load_library() -> ctypes.CDLL:
         raise FileNotFoundError(f"{SO} not built: run `python -m paper_2204_02662_amd.build`")
     lib = ctypes.CDLL(str(SO))
     P, I, I64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
-    lib.epp_prepare.argtypes = [ctypes.POINTER(_Csr), P, I64, I, P, ctypes.POINTER(P)]
-    lib.epp_prepare_full.argtypes = [ctypes.POINTER(_Csr), P, ctypes.POINTER(P)]
+    A = ctypes.POINTER(_Alloc)
+    lib.epp_prepare.argtypes = [ctypes.POINTER(_Csr), P, I64, I, A, P, ctypes.POINTER(P)]
+    lib.epp_prepare_full.argtypes = [ctypes.POINTER(_Csr), A, P, ctypes.POINTER(P)]
+    lib.epp_path_prepare_width.argtypes = [P, I, P]
     lib.epp_num_layers.argtypes = [P]
     lib.epp_get_path.argtypes = [P, I]
     lib.epp_get_path.restype = P
@@ -84,7 +126,7 @@ def load_library() -> ctypes.CDLL:
     lib.epp_weight_gradient_workspace.restype = I64
     lib.epp_weight_gradient.argtypes = [P, I, P, I, P, I, P, P, I64, P]
     lib.epp_input_gradient.argtypes = [P, I, P, I, P, I, P, P]
-    lib.epp_paths_import.argtypes = [I64, I, P, I64, ctypes.POINTER(_PathArrays), P, ctypes.POINTER(P)]
+    lib.epp_paths_import.argtypes = [I64, I, P, I64, ctypes.POINTER(_PathArrays), A, P, ctypes.POINTER(P)]
     lib.epp_destroy_paths.argtypes = [P]
     lib.epp_destroy_paths.restype = None
     lib.epp_destroy_path.argtypes = [P]
@@ -140,6 +182,14 @@ class Path_:
         self._h = handle
         self._owned = owned
         self._keepalive = keepalive
+        self._n = None
+
+    @property
+    def n(self) -> int:
+        """Vertices of the input graph (rows of the gradient matrices)."""
+        if self._n is None:
+            self._n = self.info().n
+        return self._n
 
     def info(self) -> PathInfo:
         raw = _PathInfo()
@@ -164,6 +214,11 @@ class Path_:
 
     def set_group_size(self, F: int, gs: int) -> None:
         _check(load_library().epp_path_set_group_size(self._h, F, gs, _stream()))
+
+    def prepare_width(self, F: int) -> None:
+        """One-off schedule of this path for gradient width F (allocates, synchronises); required
+        before the aggregate calls, which only enqueue."""
+        _check(load_library().epp_path_prepare_width(self._h, F, _stream()))
 
     def __del__(self):
         if getattr(self, "_owned", False) and self._h and _lib is not None:
@@ -208,20 +263,24 @@ class Paths:
 
 
 def epp_prepare(n: int, rowptr: torch.Tensor, col: torch.Tensor, val: torch.Tensor, train_ids: torch.Tensor,
-                L: int) -> Paths:
+                L: int, torch_allocator: bool = True) -> Paths:
+    """Execution paths of (graph, training set, L).  With ``torch_allocator`` every device buffer of
+    the handle comes from PyTorch's caching allocator (epp_alloc_t), otherwise from hipMalloc."""
     lib = load_library()
     csr = _csr(n, rowptr, col, val)
     _dev(train_ids, torch.int32)
     out = ctypes.c_void_p()
-    _check(lib.epp_prepare(ctypes.byref(csr), train_ids.data_ptr(), train_ids.numel(), L, _stream(), ctypes.byref(out)))
+    _check(lib.epp_prepare(ctypes.byref(csr), train_ids.data_ptr(), train_ids.numel(), L, _allocator(torch_allocator),
+                           _stream(), ctypes.byref(out)))
     return Paths(out.value)
 
 
-def epp_prepare_full(n: int, rowptr: torch.Tensor, col: torch.Tensor, val: torch.Tensor) -> Path_:
+def epp_prepare_full(n: int, rowptr: torch.Tensor, col: torch.Tensor, val: torch.Tensor,
+                     torch_allocator: bool = True) -> Path_:
     lib = load_library()
     csr = _csr(n, rowptr, col, val)
     out = ctypes.c_void_p()
-    _check(lib.epp_prepare_full(ctypes.byref(csr), _stream(), ctypes.byref(out)))
+    _check(lib.epp_prepare_full(ctypes.byref(csr), _allocator(torch_allocator), _stream(), ctypes.byref(out)))
     return Path_(out.value, owned=True)
 
 
@@ -234,6 +293,8 @@ def _grads(path: Path_, grad_in: torch.Tensor, grad_out: torch.Tensor) -> int:
     _dev(grad_in, torch.float32), _dev(grad_out, torch.float32)
     if grad_in.dim() != 2 or grad_in.shape != grad_out.shape:
         raise ValueError("grad_in and grad_out must be n x F matrices of the same shape")
+    if grad_in.shape[0] != path.n:  # the kernels index rows by vertex id: fewer rows would be read out of bounds
+        raise ValueError(f"gradient matrices have {grad_in.shape[0]} rows, the graph has {path.n} vertices")
     return grad_in.shape[1]
 
 
@@ -287,7 +348,7 @@ def epp_input_gradient(paths: Paths, k: int, grad_X: torch.Tensor, W: torch.Tens
                                              grad_Y.data_ptr(), _stream()))
 
 
-def epp_paths_import(n: int, train_ids: torch.Tensor, layers) -> Paths:
+def epp_paths_import(n: int, train_ids: torch.Tensor, layers, torch_allocator: bool = True) -> Paths:
     """Handle from saved paths: ``layers[l]`` = (row_ids, rowptr, col, val) device tensors of SG_l in the
     canonical form that ``Path_.export()`` returns."""
     _dev(train_ids, torch.int32)
@@ -299,6 +360,6 @@ def epp_paths_import(n: int, train_ids: torch.Tensor, layers) -> Paths:
         arr[l] = _PathArrays(row_ids.numel(), col.numel(), row_ids.data_ptr(), rowptr.data_ptr(), col.data_ptr(),
                              val.data_ptr())
     out = ctypes.c_void_p()
-    _check(load_library().epp_paths_import(n, len(layers), train_ids.data_ptr(), train_ids.numel(), arr, _stream(),
-                                           ctypes.byref(out)))
+    _check(load_library().epp_paths_import(n, len(layers), train_ids.data_ptr(), train_ids.numel(), arr,
+                                           _allocator(torch_allocator), _stream(), ctypes.byref(out)))
     return Paths(out.value)

@@ -25,18 +25,5 @@ def build(verbose: bool = False) -> Path:
     return SO
 
 
-def build_tools(verbose: bool = False) -> Path:
-    """Stand-alone measurement tool: random-row gather rate of the memory hierarchy."""
-    src = PKG / "tools" / "gather_rate.hip"
-    exe = PKG / "tools" / "gather_rate"
-    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           str(src), "-o", str(exe)]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
-    return exe
-
-
 if __name__ == "__main__":
     build(verbose=True)
-    build_tools(verbose=True)

@@ -515,11 +515,12 @@ int epp_build_schedule(epp_path* p, int gs, hipStream_t s, Schedule** out) {
     const int64_t n_groups = (p->nnz + gs - 1) / gs;
     if (n_groups >= 0x7FFFFFFFll) { epp_set_error("too many groups"); return EPP_ERR_TOO_LARGE; }
     sc->n_groups = n_groups;
-    EPP_TRY(sc->group_row.alloc((size_t)n_groups * 4));
-    EPP_TRY(sc->cut_rows.alloc((size_t)n_groups * 4));
+    const epp_alloc_t* al = epp_alloc_of(p);
+    EPP_TRY(sc->group_row.alloc((size_t)n_groups * 4, al));
+    EPP_TRY(sc->cut_rows.alloc((size_t)n_groups * 4, al));
     if (n_groups > 0) {
         DevBuf cnt;
-        EPP_TRY(cnt.alloc(sizeof(unsigned int)));
+        EPP_TRY(cnt.alloc(sizeof(unsigned int), al));
         EPP_HIP_TRY(hipMemsetAsync(cnt.p, 0, sizeof(unsigned int), s));
         hipLaunchKernelGGL(k_sched_groups, dim3((unsigned)((n_groups + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
                            p->rowptr.as<int32_t>(), p->n_stream_rows, gs, n_groups, sc->group_row.as<int32_t>(),
@@ -567,7 +568,7 @@ int epp_launch_aggregate(epp_path* p, Schedule* sc, int log2_slices, const float
         a.F = F;
         a.gs = sc->gs;
         a.log2ns = log2ns;
-        a.has_cold = p->cold_thr > 0;
+        a.has_cold = p->cold_thr > 0 && (int64_t)F * 4 >= 256;  // narrow rows ignore the marks (bit 30 is masked)
         a.pieces = pieces;
         a.row_bits = row_bits;
         a.src_bits = src_bits;
@@ -614,7 +615,7 @@ int epp_tune_locality(epp_path* p, int F, hipStream_t s, int* log2_slices) {
         // counts, histogram and hot bitmap share one allocation
         const size_t hot_bytes = (size_t)((p->n + 63) / 64) * 8;
         EPP_TRY(arena.reserve(DevArena::rounded((size_t)p->n * 4) + DevArena::rounded(kCountBins * sizeof(unsigned long long)) +
-                              DevArena::rounded(hot_bytes)));
+                              DevArena::rounded(hot_bytes), epp_alloc_of(p)));
         arena.take(&cnt, (size_t)p->n * 4);
         EPP_HIP_TRY(hipMemsetAsync(cnt.p, 0, cnt.bytes, s));
         DevBuf hist;
@@ -657,6 +658,12 @@ int epp_tune_locality(epp_path* p, int F, hipStream_t s, int* log2_slices) {
             if (refs_between >= 0.06 * (double)p->nnz / (double)stride) *log2_slices = 1;
         }
     }
+    // One set of marks per path, shared by all its widths: it is the one chosen for the largest
+    // prepared width that marks at all (a smaller budget in rows; narrower widths then stream a
+    // few rows they could have kept).  The marks therefore depend on which widths have been
+    // prepared, never on the order of the calls.
+    if (thr == 0 || F <= p->cold_F) return EPP_OK;
+    p->cold_F = F;
     if (thr == p->cold_thr) return EPP_OK;
     if (thr > 0) {
         hipLaunchKernelGGL(k_hot_bitmap, dim3((unsigned)((p->n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,

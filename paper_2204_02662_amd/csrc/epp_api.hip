@@ -22,29 +22,42 @@ Schedule* find_schedule(epp_path* p, int gs) {
     return nullptr;
 }
 
-int ensure_schedule(epp_path* p, int F, hipStream_t s, epp_path::WidthCfg** out) {
+// One-off work of a (path, width): group table, partial rows, locality marks.  Allocates and
+// waits; the aggregate entry points only look the result up.
+int prepare_width(epp_path* p, int F, hipStream_t s, epp_path::WidthCfg** out) {
     epp_path::WidthCfg* w = width_cfg(p, F);
     if (!w->sched) {
         const int gs = w->forced_gs > 0 ? w->forced_gs : epp_default_group_size(p, F);
         Schedule* sc = find_schedule(p, gs);
         if (!sc) EPP_TRY(epp_build_schedule(p, gs, s, &sc));
-        EPP_TRY(sc->ensure_pieces(F));
+        EPP_TRY(sc->ensure_pieces(F, epp_alloc_of(p)));
         EPP_TRY(epp_tune_locality(p, F, s, &w->log2_slices));
         w->sched = sc;
     }
     p->last_F = F;
-    *out = w;
+    if (out) *out = w;
+    return EPP_OK;
+}
+
+int check_width(int F) {
+    if (F < 1) { epp_set_error("F must be >= 1 (got %d)", F); return EPP_ERR_INVALID_ARG; }
     return EPP_OK;
 }
 
 int aggregate(epp_path* p, const float* in, float* out, int F, hipStream_t s, const unsigned int* row_bits = nullptr,
               const unsigned int* src_bits = nullptr) {
     if (!p || !in || !out) { epp_set_error("NULL argument"); return EPP_ERR_INVALID_ARG; }
-    if (F < 1) { epp_set_error("F must be >= 1 (got %d)", F); return EPP_ERR_INVALID_ARG; }
+    EPP_TRY(check_width(F));
     if ((int64_t)p->n * F >= (1ll << 40)) { epp_set_error("gradient matrix too large"); return EPP_ERR_TOO_LARGE; }
     if (in == out) { epp_set_error("grad_in and grad_out must not alias"); return EPP_ERR_INVALID_ARG; }
-    epp_path::WidthCfg* w = nullptr;
-    EPP_TRY(ensure_schedule(p, F, s, &w));
+    const epp_path::WidthCfg* w = nullptr;
+    for (const auto& x : p->widths)
+        if (x.F == F && x.sched) w = &x;
+    if (!w) {
+        epp_set_error("width F=%d has not been prepared on this path: call epp_path_prepare_width first", F);
+        return EPP_ERR_INVALID_ARG;
+    }
+    p->last_F = F;
     return epp_launch_aggregate(p, w->sched, w->log2_slices, in, out, F, s, row_bits, src_bits);
 }
 
@@ -112,7 +125,14 @@ extern "C" int epp_path_set_group_size(epp_path_t* p, int F, int gs, epp_stream_
         for (const auto& x : p->widths) used |= (x.sched == p->scheds[i]);
         if (!used) { delete p->scheds[i]; p->scheds.erase(p->scheds.begin() + i); } else ++i;
     }
-    return ensure_schedule(p, F, (hipStream_t)stream, &w);
+    return prepare_width(p, F, (hipStream_t)stream, nullptr);
+}
+
+extern "C" int epp_path_prepare_width(epp_path_t* p, int F, epp_stream_t stream) {
+    if (!p) { epp_set_error("path is NULL"); return EPP_ERR_INVALID_ARG; }
+    EPP_TRY(check_width(F));
+    if ((int64_t)p->n * F >= (1ll << 40)) { epp_set_error("gradient matrix too large"); return EPP_ERR_TOO_LARGE; }
+    return prepare_width(p, F, (hipStream_t)stream, nullptr);
 }
 
 extern "C" int epp_backward_aggregate(epp_path_t* p, const float* grad_in, float* grad_out, int F,

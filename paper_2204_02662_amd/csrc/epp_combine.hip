@@ -255,13 +255,13 @@ int check_widths(int Fi, int Fo) {
 }
 
 // Row set of the products: N^k, or every vertex for k = -1.
-int row_set(epp_paths* p, int k, hipStream_t s, const int32_t** ids, int64_t* count) {
+int row_set(const epp_paths* p, int k, const int32_t** ids, int64_t* count) {
     if (k == -1) {
         *ids = nullptr;
         *count = p->n;
         return EPP_OK;
     }
-    return epp_active_ids(p, k, s, ids, count);
+    return epp_active_ids(p, k, ids, count);
 }
 
 // Rows per partial sum: enough chunks to fill the chip a few times over, whole steps each.
@@ -300,7 +300,7 @@ extern "C" int epp_weight_gradient(epp_paths_t* paths, int k, const float* Y, in
     hipStream_t s = (hipStream_t)stream;
     const int32_t* ids = nullptr;
     int64_t n_rows = 0;
-    EPP_TRY(row_set(paths, k, s, &ids, &n_rows));
+    EPP_TRY(row_set(paths, k, &ids, &n_rows));
     int64_t per, chunks;
     chunking(n_rows, F_in, F_out, &per, &chunks);
     if (chunks > 0) {
@@ -344,7 +344,7 @@ extern "C" int epp_input_gradient(epp_paths_t* paths, int k, const float* grad_X
     hipStream_t s = (hipStream_t)stream;
     const int32_t* ids = nullptr;
     int64_t n_rows = 0;
-    EPP_TRY(row_set(paths, k, s, &ids, &n_rows));
+    EPP_TRY(row_set(paths, k, &ids, &n_rows));
     if (n_rows == 0) return EPP_OK;
     // rows are the long dimension: 128 of them per tile
     const TileShape shape = tile_shape(1 << 20, F_in);

@@ -30,30 +30,44 @@ void epp_set_error(const char* fmt, ...);
         if (epp_rc_ != EPP_OK) return epp_rc_; \
     } while (0)
 
-// Device allocation that frees itself; `bytes` is kept for the footprint report.  A buffer can
-// also be a view of part of another allocation (temporaries carved from one arena: every
-// hipMalloc / hipFree pair costs about 0.15 ms, hipFree waits for the device).
+// Device allocation that frees itself; `bytes` is kept for the footprint report.  The memory
+// comes from the caller's allocator (epp_alloc_t, the handle keeps a copy) or, without one, from
+// hipMalloc.  A buffer can also be a view of part of another allocation (temporaries carved from
+// one arena: every hipMalloc / hipFree pair costs about 0.15 ms, hipFree waits for the device).
 struct DevBuf {
     void* p = nullptr;
     size_t bytes = 0;
     bool owned = true;
+    epp_alloc_t via = {nullptr, nullptr, nullptr};  // allocator that owns p (alloc == NULL: hipMalloc)
     DevBuf() = default;
     DevBuf(const DevBuf&) = delete;
     DevBuf& operator=(const DevBuf&) = delete;
-    DevBuf(DevBuf&& o) noexcept : p(o.p), bytes(o.bytes), owned(o.owned) { o.p = nullptr; o.bytes = 0; }
+    DevBuf(DevBuf&& o) noexcept : p(o.p), bytes(o.bytes), owned(o.owned), via(o.via) { o.p = nullptr; o.bytes = 0; }
     DevBuf& operator=(DevBuf&& o) noexcept {
-        if (this != &o) { release(); p = o.p; bytes = o.bytes; owned = o.owned; o.p = nullptr; o.bytes = 0; }
+        if (this != &o) { release(); p = o.p; bytes = o.bytes; owned = o.owned; via = o.via; o.p = nullptr; o.bytes = 0; }
         return *this;
     }
     ~DevBuf() { release(); }
-    int alloc(size_t n) {
+    int alloc(size_t n, const epp_alloc_t* a) {
         release();
         if (n == 0) n = 4;  // keep a valid pointer for empty arrays
-        if (hipMalloc(&p, n) != hipSuccess) {
-            (void)hipGetLastError();
-            p = nullptr;
-            epp_set_error("device allocation of %zu bytes failed", n);
-            return EPP_ERR_ALLOC;
+        if (a && a->alloc && a->free) {
+            p = a->alloc(n, a->ctx);
+            if (!p || (reinterpret_cast<uintptr_t>(p) & 255)) {
+                if (p) a->free(p, a->ctx);
+                p = nullptr;
+                epp_set_error("the caller's allocator gave no 256-byte aligned block of %zu bytes", n);
+                return EPP_ERR_ALLOC;
+            }
+            via = *a;
+        } else {
+            if (hipMalloc(&p, n) != hipSuccess) {
+                (void)hipGetLastError();
+                p = nullptr;
+                epp_set_error("device allocation of %zu bytes failed", n);
+                return EPP_ERR_ALLOC;
+            }
+            via = {nullptr, nullptr, nullptr};
         }
         bytes = n;
         owned = true;
@@ -66,7 +80,10 @@ struct DevBuf {
         owned = false;
     }
     void release() {
-        if (p && owned) (void)hipFree(p);
+        if (p && owned) {
+            if (via.alloc) via.free(p, via.ctx);
+            else (void)hipFree(p);
+        }
         p = nullptr;
         bytes = 0;
         owned = true;
@@ -79,7 +96,7 @@ struct DevArena {
     DevBuf store;
     size_t used = 0;
     static size_t rounded(size_t n) { return (std::max<size_t>(n, 4) + 255) & ~(size_t)255; }
-    int reserve(size_t total) { used = 0; return store.alloc(total); }
+    int reserve(size_t total, const epp_alloc_t* a) { used = 0; return store.alloc(total, a); }
     void take(DevBuf* b, size_t n) {
         b->view(static_cast<char*>(store.p) + used, n);
         used += rounded(n);
@@ -107,15 +124,15 @@ struct Schedule {
             if (q->F == F) return q->buf.as<float>();
         return nullptr;
     }
-    int ensure_pieces(int F) {
+    int ensure_pieces(int F, const epp_alloc_t* a) {
         if (pieces_for(F) || n_split_rows == 0) return EPP_OK;
         Pieces* q = new Pieces();
         q->F = F;
-        if (q->buf.alloc((size_t)n_groups * 2 * (size_t)F * sizeof(float)) != EPP_OK) { delete q; return EPP_ERR_ALLOC; }
+        if (q->buf.alloc((size_t)n_groups * 2 * (size_t)F * sizeof(float), a) != EPP_OK) { delete q; return EPP_ERR_ALLOC; }
         pieces.push_back(q);
         return EPP_OK;
     }
-    void drop_pieces(int F) {  // hipFree waits for the device, so no launch can still be using them
+    void drop_pieces(int F) {  // (hipFree waits for the device; a caller's allocator must be stream-ordered)
         for (size_t i = 0; i < pieces.size(); ++i)
             if (pieces[i]->F == F) { delete pieces[i]; pieces.erase(pieces.begin() + i); return; }
     }
@@ -141,13 +158,16 @@ struct epp_path {
     DevBuf rowptr;               // int32[n_stream_rows + 1]
     DevBuf cv;                   // int2[nnz]: (column id | cold flag bit 30 | row-end flag bit 31, weight bits)
     int cold_thr = 0;            // entries whose source is referenced fewer times than this carry the cold flag
+    int cold_F = 0;              // width the cold flags were chosen for (the largest prepared width that marks)
+    epp_alloc_t alloc = {nullptr, nullptr, nullptr};  // the caller's allocator (alloc == NULL: hipMalloc)
     // all-active graph only
     DevBuf full_rowptr;          // int32[n + 1] as given (for export)
     int64_t n_empty_rows = 0;
     DevBuf empty_rows;           // int32[n_empty_rows] vertices with empty lists
     std::vector<Schedule*> scheds;
     // per-width choices
-    struct WidthCfg { int F; int forced_gs; Schedule* sched; int log2_slices; };  // slices: XCD feature slicing
+    // sched == NULL: the width has not been prepared (epp_path_prepare_width); slices: XCD feature slicing
+    struct WidthCfg { int F; int forced_gs; Schedule* sched; int log2_slices; };
     std::vector<WidthCfg> widths;
     int last_F = 0;
     ~epp_path() { for (Schedule* s : scheds) delete s; }
@@ -159,8 +179,8 @@ struct epp_paths {
     std::vector<DevBuf> bitmaps;    // L+1 bitmaps of N^k, uint64 words
     std::vector<int64_t> set_size;  // |N^k|
     std::vector<epp_path*> path;    // index l; once the sets stop growing, deeper layers share one object
-    DevBuf set0_ids;                // ascending ids of N^0, built on first use (the other sets are path rows)
-    bool have_set0_ids = false;
+    DevBuf set0_ids;                // ascending ids of N^0 (the other sets are path rows)
+    epp_alloc_t alloc = {nullptr, nullptr, nullptr};
     ~epp_paths() {
         for (size_t i = 0; i < path.size(); ++i) {
             bool seen = false;
@@ -176,8 +196,8 @@ struct epp_paths {
 // without waiting; the caller hands them to epp_path_set_stats after it has synchronised
 int epp_path_finish(epp_path* p, hipStream_t s, void* stats_scratch = nullptr, unsigned long long* host_later = nullptr);
 void epp_path_set_stats(epp_path* p, const unsigned long long* host);
-// ascending vertex ids of N^k (device, owned by `p`); the first call for k = 0 synchronises
-int epp_active_ids(epp_paths* p, int k, hipStream_t s, const int32_t** ids, int64_t* count);
+// ascending vertex ids of N^k (device, owned by `p`); allocates nothing, never waits
+int epp_active_ids(const epp_paths* p, int k, const int32_t** ids, int64_t* count);
 
 // aggregate.hip
 int epp_build_schedule(epp_path* p, int gs, hipStream_t s, Schedule** out);
@@ -185,3 +205,5 @@ int epp_launch_aggregate(epp_path* p, Schedule* sc, int log2_slices, const float
                          const unsigned int* row_bits = nullptr, const unsigned int* src_bits = nullptr);
 int epp_default_group_size(const epp_path* p, int F);
 int epp_tune_locality(epp_path* p, int F, hipStream_t s, int* log2_slices);
+inline const epp_alloc_t* epp_alloc_of(const epp_path* p) { return p->alloc.alloc ? &p->alloc : nullptr; }
+inline const epp_alloc_t* epp_alloc_of(const epp_paths* p) { return p->alloc.alloc ? &p->alloc : nullptr; }

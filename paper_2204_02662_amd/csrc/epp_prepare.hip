@@ -74,10 +74,14 @@ __global__ __launch_bounds__(kBlock) void k_mark_training(const int32_t* __restr
 // kept at the previous level has its column in N^{k-1}, hence in N^k, and is kept again: only
 // the other entries are loaded and looked up.  Once the sets are close to saturation this
 // turns a pass bound by the rate of random bitmap lookups into a scan of the previous mask.
+//
+// Columns are range-checked where they are loaded (every entry at the first level): an id outside
+// [0, n) raises bit 1 of *err and is treated as not kept, so it is never used as an index.
 __global__ __launch_bounds__(kBlock) void k_edge_mask(const int32_t* __restrict__ col, int64_t nnz, int64_t n_seg,
-                                                      const unsigned int* __restrict__ bitmap32, int have_prev,
-                                                      const int* __restrict__ not_subset,
-                                                      unsigned long long* mask, int* __restrict__ tile_count) {
+                                                      int64_t n, const unsigned int* __restrict__ bitmap32,
+                                                      int have_prev, const int* __restrict__ not_subset,
+                                                      unsigned long long* mask, int* __restrict__ tile_count,
+                                                      int* __restrict__ err) {
     __shared__ int wave_cnt[4];
     const int wave = threadIdx.x >> 6, lane = lane_id();
     int cnt = 0;
@@ -99,6 +103,13 @@ __global__ __launch_bounds__(kBlock) void k_edge_mask(const int32_t* __restrict_
         const int64_t e = (seg0 + i) * 64 + lane;
         c[i] = (e < nnz && !known[i]) ? col[e] : -1;
     }
+    bool bad = false;
+#pragma unroll
+    for (int i = 0; i < kPerWave; ++i) {
+        const int64_t e = (seg0 + i) * 64 + lane;
+        if (e < nnz && !known[i] && (c[i] < 0 || c[i] >= n)) { bad = true; c[i] = -1; }
+    }
+    if (bad) atomicOr(err, 2);
 #pragma unroll
     for (int i = 0; i < kPerWave; ++i) w[i] = c[i] >= 0 ? bitmap32[c[i] >> 5] : 0u;
 #pragma unroll
@@ -212,18 +223,25 @@ __global__ __launch_bounds__(kBlock) void k_edge_extract(const int32_t* __restri
     }
 }
 
-// Filtered row pointer of every vertex and membership of N^{k+1}.
+// Filtered row pointer of every vertex and membership of N^{k+1}.  A row pointer that does not
+// rise from 0 to nnz raises bit 0 of *err; the offending row is treated as empty, so no index
+// outside the mask arrays is formed.
 __global__ __launch_bounds__(kBlock) void k_row_flags(const int32_t* __restrict__ rowptr, int64_t n, int64_t nnz,
                                                       const unsigned long long* __restrict__ mask,
                                                       const int* __restrict__ seg_base,
                                                       const long long* __restrict__ total_p,
                                                       int* __restrict__ newptr,
-                                                      unsigned long long* __restrict__ bitmap_next) {
+                                                      unsigned long long* __restrict__ bitmap_next,
+                                                      int* __restrict__ err) {
     int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     bool flag = false;
     if (v < n) {
         const int total = (int)*total_p;  // kept entries of the level (the host has not read it yet)
         int64_t p0 = rowptr[v], p1 = rowptr[v + 1];
+        if (p0 < 0 || p1 < p0 || p1 > nnz || (v == 0 && p0 != 0) || (v == n - 1 && p1 != nnz)) {
+            atomicOr(err, 1);
+            p0 = p1 = nnz;
+        }
         int a = p0 >= nnz ? total : seg_base[p0 >> 6] + __popcll(mask[p0 >> 6] & low_mask((int)(p0 & 63)));
         int b = p1 >= nnz ? total : seg_base[p1 >> 6] + __popcll(mask[p1 >> 6] & low_mask((int)(p1 & 63)));
         newptr[v] = a;
@@ -309,10 +327,27 @@ __global__ __launch_bounds__(kBlock) void k_len_hist(const int32_t* __restrict__
 }
 
 // Interleave a plain CSR's (col, val) into pairs (all-active graph).
+// A column outside [0, n) raises bit 1 of *err (if given) and is stored as 0.
 __global__ __launch_bounds__(kBlock) void k_interleave(const int32_t* __restrict__ col, const float* __restrict__ val,
-                                                       int64_t nnz, int2* __restrict__ cv) {
+                                                       int64_t nnz, int64_t n, int2* __restrict__ cv,
+                                                       int* __restrict__ err) {
     int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (e < nnz) cv[e] = make_int2(col[e], __float_as_int(val[e]));
+    if (e >= nnz) return;
+    int32_t c = col[e];
+    if (c < 0 || c >= n) {
+        if (err) atomicOr(err, 2);
+        c = 0;
+    }
+    cv[e] = make_int2(c, __float_as_int(val[e]));
+}
+
+// Row pointer of a whole graph: must rise from 0 to nnz (bit 0 of *err otherwise).
+__global__ __launch_bounds__(kBlock) void k_check_rowptr(const int32_t* __restrict__ rowptr, int64_t n, int64_t nnz,
+                                                         int* __restrict__ err) {
+    int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (v >= n) return;
+    const int64_t p0 = rowptr[v], p1 = rowptr[v + 1];
+    if (p0 < 0 || p1 < p0 || p1 > nnz || (v == 0 && p0 != 0) || (v == n - 1 && p1 != nnz)) atomicOr(err, 1);
 }
 
 __global__ __launch_bounds__(kBlock) void k_deinterleave(const int2* __restrict__ cv, int64_t nnz, int32_t* __restrict__ col,
@@ -414,7 +449,7 @@ int validate_csr(const epp_csr_t* g) {
 // Ascending ids of a bitmap (and optionally the compact row pointer).  Returns the count.
 int compact_bitmap(const DevBuf& bitmap, int64_t n, const int* newptr, int total_nnz, DevBuf* ids, DevBuf* ptr_out,
                    int64_t* count, DevBuf& tile_cnt, DevBuf& tile_base, DevBuf& dev_total, HostScalars& hs,
-                   hipStream_t s) {
+                   const epp_alloc_t* al, hipStream_t s) {
     const int64_t n_words = (n + 63) / 64;
     const unsigned tiles = grid_for(n_words, kWordsPerTile);
     long long R = 0;
@@ -429,8 +464,8 @@ int compact_bitmap(const DevBuf& bitmap, int64_t n, const int* newptr, int total
     }
     *count = R;
     if (!ids) return EPP_OK;
-    EPP_TRY(ids->alloc((size_t)R * sizeof(int32_t)));
-    if (ptr_out) EPP_TRY(ptr_out->alloc((size_t)(R + 1) * sizeof(int32_t)));
+    EPP_TRY(ids->alloc((size_t)R * sizeof(int32_t), al));
+    if (ptr_out) EPP_TRY(ptr_out->alloc((size_t)(R + 1) * sizeof(int32_t), al));
     if (tiles) {
         hipLaunchKernelGGL(k_bitmap_compact, dim3(tiles), dim3(kBlock), 0, s, bitmap.as<unsigned long long>(), n_words,
                            tile_base.as<int>(), newptr, ids->as<int32_t>(),
@@ -464,6 +499,13 @@ __global__ __launch_bounds__(kBlock) void k_check_cols(const int32_t* __restrict
     if (e < nnz && (col[e] < 0 || col[e] >= n)) atomicOr(err, 2);
 }
 
+// Message and code for the error bits raised by the input checks (bit 0 row pointer, bit 1 ids).
+int input_error(int bits, int64_t n) {
+    if (bits & 2) { epp_set_error("a column id lies outside [0, %lld)", (long long)n); return EPP_ERR_OUT_OF_RANGE_ID; }
+    epp_set_error("the row pointer does not rise from 0 to nnz");
+    return EPP_ERR_INVALID_ARG;
+}
+
 }  // namespace
 
 void epp_path_set_stats(epp_path* p, const unsigned long long* host) {
@@ -476,7 +518,7 @@ void epp_path_set_stats(epp_path* p, const unsigned long long* host) {
 int epp_path_finish(epp_path* p, hipStream_t s, void* stats_scratch, unsigned long long* host_later) {
     DevBuf stats;
     if (stats_scratch) stats.view(stats_scratch, (EPP_NCLASS + 1) * sizeof(unsigned long long));
-    else EPP_TRY(stats.alloc((EPP_NCLASS + 1) * sizeof(unsigned long long)));
+    else EPP_TRY(stats.alloc((EPP_NCLASS + 1) * sizeof(unsigned long long), epp_alloc_of(p)));
     EPP_HIP_TRY(hipMemsetAsync(stats.p, 0, stats.bytes, s));
     if (p->n_rows > 0) {
         // canonical rows: the all-active graph counts its empty rows too
@@ -505,7 +547,7 @@ int epp_path_finish(epp_path* p, hipStream_t s, void* stats_scratch, unsigned lo
 }
 
 extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t n_train, int L,
-                           epp_stream_t stream, epp_paths_t** out) {
+                           const epp_alloc_t* alloc, epp_stream_t stream, epp_paths_t** out) {
     if (!out) { epp_set_error("out is NULL"); return EPP_ERR_INVALID_ARG; }
     *out = nullptr;
     EPP_TRY(validate_csr(g));
@@ -527,11 +569,13 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
     struct Guard { epp_paths* p; ~Guard() { delete p; } } guard{P};
     P->L = L;
     P->n = n;
+    if (alloc && alloc->alloc && alloc->free) P->alloc = *alloc;
+    const epp_alloc_t* al = epp_alloc_of(P);
     P->bitmaps.resize(L + 1);
     P->set_size.assign(L + 1, 0);
     P->path.assign(L, nullptr);
     for (int k = 0; k <= L; ++k) {
-        EPP_TRY(P->bitmaps[k].alloc((size_t)n_words * 8));
+        EPP_TRY(P->bitmaps[k].alloc((size_t)n_words * 8, al));
         EPP_HIP_TRY(hipMemsetAsync(P->bitmaps[k].p, 0, P->bitmaps[k].bytes, s));
     }
 
@@ -543,14 +587,14 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
     EPP_TRY(arena.reserve(DevArena::rounded((size_t)n_seg * 8) + DevArena::rounded((size_t)n_seg * 4) +
                           2 * DevArena::rounded(max_tiles * 4) + DevArena::rounded(scan_tmp_bytes(edge_tiles)) +
                           DevArena::rounded((size_t)(n + 1) * 4) +
-                          3 * DevArena::rounded(16) + DevArena::rounded(stats_bytes)));
+                          3 * DevArena::rounded(32) + DevArena::rounded(stats_bytes), al));
     arena.take(&mask, (size_t)n_seg * 8);
     arena.take(&seg_base, (size_t)n_seg * 4);
     arena.take(&tile_cnt, max_tiles * 4);
     arena.take(&tile_base, max_tiles * 4);
     arena.take(&scan_tmp, scan_tmp_bytes(edge_tiles));
     arena.take(&newptr, (size_t)(n + 1) * 4);
-    arena.take(&dev_total, 2 * sizeof(long long));  // [0] kept entries, [1] rows of the level
+    arena.take(&dev_total, 3 * sizeof(long long));  // [0] kept entries, [1] rows of the level, [2] input error bits
     arena.take(&err, sizeof(int));
     arena.take(&not_subset, sizeof(int));
     arena.take(&stats, stats_bytes);
@@ -570,8 +614,9 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
             return EPP_ERR_OUT_OF_RANGE_ID;
         }
     }
-    EPP_TRY(compact_bitmap(P->bitmaps[0], n, nullptr, 0, nullptr, nullptr, &P->set_size[0], tile_cnt, tile_base,
-                           dev_total, hs, s));
+    // ascending ids of N^0 (the other sets are the row ids of the paths)
+    EPP_TRY(compact_bitmap(P->bitmaps[0], n, nullptr, 0, &P->set0_ids, nullptr, &P->set_size[0], tile_cnt, tile_base,
+                           dev_total, hs, al, s));
 
     // One level: everything that only needs the two counts (kept entries, rows) on the device is
     // enqueued first, the host waits once for both, makes one allocation for the path's three
@@ -584,9 +629,11 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
         P->path[l] = p;
         built.push_back(p);
         p->n = n;
+        p->alloc = P->alloc;
         p->n_src = P->set_size[k];
         long long* d_total = dev_total.as<long long>();
-        EPP_HIP_TRY(hipMemsetAsync(d_total, 0, 2 * sizeof(long long), s));
+        int* d_err = reinterpret_cast<int*>(d_total + 2);
+        EPP_HIP_TRY(hipMemsetAsync(d_total, 0, 3 * sizeof(long long), s));
         if (edge_tiles) {
             // from the second level on the mask of the level before is reused where N^{k-1} lies in N^k
             if (k > 0) {
@@ -595,9 +642,9 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
                                    P->bitmaps[k - 1].as<unsigned long long>(), P->bitmaps[k].as<unsigned long long>(),
                                    n_words, not_subset.as<int>());
             }
-            hipLaunchKernelGGL(k_edge_mask, dim3(edge_tiles), dim3(kBlock), 0, s, g->col, nnz, n_seg,
+            hipLaunchKernelGGL(k_edge_mask, dim3(edge_tiles), dim3(kBlock), 0, s, g->col, nnz, n_seg, n,
                                P->bitmaps[k].as<unsigned int>(), k > 0 ? 1 : 0, not_subset.as<int>(),
-                               mask.as<unsigned long long>(), tile_cnt.as<int>());
+                               mask.as<unsigned long long>(), tile_cnt.as<int>(), d_err);
             scan_counts(tile_cnt.as<int>(), tile_base.as<int>(), (int64_t)edge_tiles, d_total, scan_tmp.as<int>(), s);
             hipLaunchKernelGGL(k_seg_base, dim3(edge_tiles), dim3(64), 0, s, mask.as<unsigned long long>(), n_seg,
                                tile_base.as<int>(), seg_base.as<int>());
@@ -606,7 +653,7 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
         if (n > 0) {
             hipLaunchKernelGGL(k_row_flags, dim3(grid_for(n, kBlock)), dim3(kBlock), 0, s, g->rowptr, n, nnz,
                                mask.as<unsigned long long>(), seg_base.as<int>(), (const long long*)d_total,
-                               newptr.as<int>(), P->bitmaps[k + 1].as<unsigned long long>());
+                               newptr.as<int>(), P->bitmaps[k + 1].as<unsigned long long>(), d_err);
             // rows of the level: set bits of the new bitmap, counted per tile of words and scanned
             // (the edge-tile offsets are no longer needed: seg_base holds them)
             hipLaunchKernelGGL(k_bitmap_count, dim3(word_tiles), dim3(kBlock), 0, s,
@@ -615,8 +662,10 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
                                (int64_t)word_tiles, d_total + 1);
             EPP_HIP_TRY(hipGetLastError());
         }
-        EPP_HIP_TRY(hipMemcpyAsync(hs.p, d_total, 2 * sizeof(long long), hipMemcpyDeviceToHost, s));
+        EPP_HIP_TRY(hipMemcpyAsync(hs.p, d_total, 3 * sizeof(long long), hipMemcpyDeviceToHost, s));
         EPP_HIP_TRY(hipStreamSynchronize(s));
+        if (hs.p[2] != 0) return input_error((int)hs.p[2], n);
+        if (n == 0 && nnz > 0) return input_error(2, n);
         const long long kept = hs.p[0], R = hs.p[1];
         p->nnz = kept;
         p->n_rows = R;
@@ -624,7 +673,7 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
         P->set_size[k + 1] = R;
         // entries | row ids | row pointer, each 256-byte aligned
         const size_t cv_bytes = (size_t)kept * sizeof(int2), ids_bytes = (size_t)R * 4, ptr_bytes = (size_t)(R + 1) * 4;
-        EPP_TRY(p->store.alloc(DevArena::rounded(cv_bytes) + DevArena::rounded(ids_bytes) + DevArena::rounded(ptr_bytes)));
+        EPP_TRY(p->store.alloc(DevArena::rounded(cv_bytes) + DevArena::rounded(ids_bytes) + DevArena::rounded(ptr_bytes), al));
         char* base = p->store.as<char>();
         p->cv.view(base, cv_bytes);
         p->row_ids.view(base + DevArena::rounded(cv_bytes), ids_bytes);
@@ -674,7 +723,8 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
     return EPP_OK;
 }
 
-extern "C" int epp_prepare_full(const epp_csr_t* g, epp_stream_t stream, epp_path_t** out) {
+extern "C" int epp_prepare_full(const epp_csr_t* g, const epp_alloc_t* alloc, epp_stream_t stream,
+                                epp_path_t** out) {
     if (!out) { epp_set_error("out is NULL"); return EPP_ERR_INVALID_ARG; }
     *out = nullptr;
     EPP_TRY(validate_csr(g));
@@ -686,31 +736,47 @@ extern "C" int epp_prepare_full(const epp_csr_t* g, epp_stream_t stream, epp_pat
     p->nnz = g->nnz;
     p->n_src = g->n;
     p->all_rows = true;
-    EPP_TRY(p->full_rowptr.alloc((size_t)(g->n + 1) * 4));
-    EPP_TRY(p->cv.alloc((size_t)g->nnz * sizeof(int2)));
-    EPP_HIP_TRY(hipMemcpyAsync(p->full_rowptr.p, g->rowptr, (size_t)(g->n + 1) * 4, hipMemcpyDeviceToDevice, s));
-    if (g->nnz > 0) {
-        hipLaunchKernelGGL(k_interleave, dim3(grid_for(g->nnz, kBlock)), dim3(kBlock), 0, s, g->col, g->val, g->nnz,
-                           p->cv.as<int2>());
-        EPP_HIP_TRY(hipGetLastError());
-    }
+    if (alloc && alloc->alloc && alloc->free) p->alloc = *alloc;
+    const epp_alloc_t* al = epp_alloc_of(p);
+    EPP_TRY(p->full_rowptr.alloc((size_t)(g->n + 1) * 4, al));
+    EPP_TRY(p->cv.alloc((size_t)g->nnz * sizeof(int2), al));
     {   // streamed form: the vertices with non-empty lists, ascending, with a compact row pointer
         HostScalars hs;
         EPP_TRY(hs.init());
-        DevBuf bitmap, tile_cnt, tile_base, dev_total;
+        DevBuf bitmap, tile_cnt, tile_base, dev_total, err;
         const int64_t n_words = (g->n + 63) / 64;
         const size_t tiles = std::max<size_t>(grid_for(n_words, kWordsPerTile), 1);
-        EPP_TRY(bitmap.alloc((size_t)n_words * 8));
-        EPP_TRY(tile_cnt.alloc(tiles * 4));
-        EPP_TRY(tile_base.alloc(tiles * 4));
-        EPP_TRY(dev_total.alloc(sizeof(long long)));
+        DevArena arena;
+        EPP_TRY(arena.reserve(DevArena::rounded((size_t)n_words * 8) + 2 * DevArena::rounded(tiles * 4) +
+                              2 * DevArena::rounded(16), al));
+        arena.take(&bitmap, (size_t)n_words * 8);
+        arena.take(&tile_cnt, tiles * 4);
+        arena.take(&tile_base, tiles * 4);
+        arena.take(&dev_total, sizeof(long long));
+        arena.take(&err, sizeof(int));
+        // the caller's arrays are checked before anything is indexed with them
+        EPP_HIP_TRY(hipMemsetAsync(err.p, 0, sizeof(int), s));
+        if (g->n > 0)
+            hipLaunchKernelGGL(k_check_rowptr, dim3(grid_for(g->n, kBlock)), dim3(kBlock), 0, s, g->rowptr, g->n, g->nnz,
+                               err.as<int>());
+        if (g->nnz > 0)
+            hipLaunchKernelGGL(k_interleave, dim3(grid_for(g->nnz, kBlock)), dim3(kBlock), 0, s, g->col, g->val, g->nnz,
+                               g->n, p->cv.as<int2>(), err.as<int>());
+        EPP_HIP_TRY(hipGetLastError());
+        EPP_HIP_TRY(hipMemcpyAsync(hs.p, err.p, sizeof(int), hipMemcpyDeviceToHost, s));
+        EPP_HIP_TRY(hipStreamSynchronize(s));
+        int herr;
+        std::memcpy(&herr, hs.p, sizeof(int));
+        if (g->n == 0 && g->nnz > 0) herr |= 2;
+        if (herr) return input_error(herr, g->n);
+        EPP_HIP_TRY(hipMemcpyAsync(p->full_rowptr.p, g->rowptr, (size_t)(g->n + 1) * 4, hipMemcpyDeviceToDevice, s));
         if (g->n > 0) {
             hipLaunchKernelGGL(k_nonempty_bitmap, dim3(grid_for(g->n, kBlock)), dim3(kBlock), 0, s, g->rowptr, g->n, 0,
                                bitmap.as<unsigned long long>());
             EPP_HIP_TRY(hipGetLastError());
         }
         EPP_TRY(compact_bitmap(bitmap, g->n, g->rowptr, (int)g->nnz, &p->row_ids, &p->rowptr, &p->n_stream_rows,
-                               tile_cnt, tile_base, dev_total, hs, s));
+                               tile_cnt, tile_base, dev_total, hs, al, s));
         p->n_empty_rows = g->n - p->n_stream_rows;
         if (p->n_empty_rows == 0) {
             EPP_HIP_TRY(hipStreamSynchronize(s));
@@ -721,7 +787,7 @@ extern "C" int epp_prepare_full(const epp_csr_t* g, epp_stream_t stream, epp_pat
             EPP_HIP_TRY(hipGetLastError());
             int64_t cnt = 0;
             EPP_TRY(compact_bitmap(bitmap, g->n, nullptr, 0, &p->empty_rows, nullptr, &cnt, tile_cnt, tile_base,
-                                   dev_total, hs, s));
+                                   dev_total, hs, al, s));
             EPP_HIP_TRY(hipStreamSynchronize(s));
         }
     }
@@ -733,7 +799,8 @@ extern "C" int epp_prepare_full(const epp_csr_t* g, epp_stream_t stream, epp_pat
 }
 
 extern "C" int epp_paths_import(int64_t n, int L, const int32_t* train_ids, int64_t n_train,
-                                const epp_path_arrays_t* layers, epp_stream_t stream, epp_paths_t** out) {
+                                const epp_path_arrays_t* layers, const epp_alloc_t* alloc, epp_stream_t stream,
+                                epp_paths_t** out) {
     if (!out) { epp_set_error("out is NULL"); return EPP_ERR_INVALID_ARG; }
     *out = nullptr;
     if (L < 1 || !layers) { epp_set_error("L must be >= 1 and layers non-NULL"); return EPP_ERR_INVALID_ARG; }
@@ -756,19 +823,21 @@ extern "C" int epp_paths_import(int64_t n, int L, const int32_t* train_ids, int6
     struct Guard { epp_paths* p; ~Guard() { delete p; } } guard{P};
     P->L = L;
     P->n = n;
+    if (alloc && alloc->alloc && alloc->free) P->alloc = *alloc;
+    const epp_alloc_t* al = epp_alloc_of(P);
     P->bitmaps.resize(L + 1);
     P->set_size.assign(L + 1, 0);
     P->path.assign(L, nullptr);
     for (int k = 0; k <= L; ++k) {
-        EPP_TRY(P->bitmaps[k].alloc((size_t)n_words * 8));
+        EPP_TRY(P->bitmaps[k].alloc((size_t)n_words * 8, al));
         EPP_HIP_TRY(hipMemsetAsync(P->bitmaps[k].p, 0, P->bitmaps[k].bytes, s));
     }
     DevBuf tile_cnt, tile_base, dev_total, err;
     const size_t tiles = std::max<size_t>(grid_for(n_words, kWordsPerTile), 1);
-    EPP_TRY(tile_cnt.alloc(tiles * 4));
-    EPP_TRY(tile_base.alloc(tiles * 4));
-    EPP_TRY(dev_total.alloc(sizeof(long long)));
-    EPP_TRY(err.alloc(2 * sizeof(int)));  // [0]: path arrays, [1]: training ids
+    EPP_TRY(tile_cnt.alloc(tiles * 4, al));
+    EPP_TRY(tile_base.alloc(tiles * 4, al));
+    EPP_TRY(dev_total.alloc(sizeof(long long), al));
+    EPP_TRY(err.alloc(2 * sizeof(int), al));  // [0]: path arrays, [1]: training ids
     EPP_HIP_TRY(hipMemsetAsync(err.p, 0, 2 * sizeof(int), s));
     if (n_train > 0)
         hipLaunchKernelGGL(k_mark_training, dim3(grid_for(n_train, kBlock)), dim3(kBlock), 0, s, train_ids, n_train, n,
@@ -788,27 +857,28 @@ extern "C" int epp_paths_import(int64_t n, int L, const int32_t* train_ids, int6
     const int herr = herr2[0] | (herr2[1] ? 2 : 0);
     if (herr & 2) { epp_set_error("an id lies outside [0, %lld)", (long long)n); return EPP_ERR_OUT_OF_RANGE_ID; }
     if (herr & 1) { epp_set_error("path arrays are not in canonical form"); return EPP_ERR_INVALID_ARG; }
-    EPP_TRY(compact_bitmap(P->bitmaps[0], n, nullptr, 0, nullptr, nullptr, &P->set_size[0], tile_cnt, tile_base,
-                           dev_total, hs, s));
+    EPP_TRY(compact_bitmap(P->bitmaps[0], n, nullptr, 0, &P->set0_ids, nullptr, &P->set_size[0], tile_cnt, tile_base,
+                           dev_total, hs, al, s));
     for (int l = L - 1; l >= 0; --l) {
         const epp_path_arrays_t& a = layers[l];
         const int k = L - l - 1;
         epp_path* p = new epp_path();
         P->path[l] = p;
         p->n = n;
+        p->alloc = P->alloc;
         p->n_rows = p->n_stream_rows = a.n_rows;
         p->nnz = a.nnz;
         p->n_src = P->set_size[k];
         P->set_size[k + 1] = a.n_rows;
-        EPP_TRY(p->row_ids.alloc((size_t)a.n_rows * 4));
-        EPP_TRY(p->rowptr.alloc((size_t)(a.n_rows + 1) * 4));
-        EPP_TRY(p->cv.alloc((size_t)a.nnz * sizeof(int2)));
+        EPP_TRY(p->row_ids.alloc((size_t)a.n_rows * 4, al));
+        EPP_TRY(p->rowptr.alloc((size_t)(a.n_rows + 1) * 4, al));
+        EPP_TRY(p->cv.alloc((size_t)a.nnz * sizeof(int2), al));
         if (a.n_rows > 0)
             EPP_HIP_TRY(hipMemcpyAsync(p->row_ids.p, a.row_ids, (size_t)a.n_rows * 4, hipMemcpyDeviceToDevice, s));
         EPP_HIP_TRY(hipMemcpyAsync(p->rowptr.p, a.rowptr, (size_t)(a.n_rows + 1) * 4, hipMemcpyDeviceToDevice, s));
         if (a.nnz > 0) {
-            hipLaunchKernelGGL(k_interleave, dim3(grid_for(a.nnz, kBlock)), dim3(kBlock), 0, s, a.col, a.val, a.nnz,
-                               p->cv.as<int2>());
+            hipLaunchKernelGGL(k_interleave, dim3(grid_for(a.nnz, kBlock)), dim3(kBlock), 0, s, a.col, a.val, a.nnz, n,
+                               p->cv.as<int2>(), (int*)nullptr);
             EPP_HIP_TRY(hipGetLastError());
         }
         EPP_TRY(epp_path_finish(p, s));
@@ -866,39 +936,23 @@ extern "C" int epp_active_set_export(const epp_paths_t* p, int k, int32_t* ids, 
     EPP_TRY(hs.init());
     DevBuf tile_cnt, tile_base, dev_total, tmp;
     const size_t tiles = std::max<size_t>(grid_for((p->n + 63) / 64, kWordsPerTile), 1);
-    EPP_TRY(tile_cnt.alloc(tiles * 4));
-    EPP_TRY(tile_base.alloc(tiles * 4));
-    EPP_TRY(dev_total.alloc(sizeof(long long)));
+    const epp_alloc_t* al = epp_alloc_of(p);
+    EPP_TRY(tile_cnt.alloc(tiles * 4, al));
+    EPP_TRY(tile_base.alloc(tiles * 4, al));
+    EPP_TRY(dev_total.alloc(sizeof(long long), al));
     int64_t c = 0;
-    EPP_TRY(compact_bitmap(p->bitmaps[k], p->n, nullptr, 0, &tmp, nullptr, &c, tile_cnt, tile_base, dev_total, hs, s));
+    EPP_TRY(compact_bitmap(p->bitmaps[k], p->n, nullptr, 0, &tmp, nullptr, &c, tile_cnt, tile_base, dev_total, hs, al, s));
     if (c > 0) EPP_HIP_TRY(hipMemcpyAsync(ids, tmp.p, (size_t)c * 4, hipMemcpyDeviceToDevice, s));
     EPP_HIP_TRY(hipStreamSynchronize(s));
     *count = c;
     return EPP_OK;
 }
 
-int epp_active_ids(epp_paths* p, int k, hipStream_t s, const int32_t** ids, int64_t* count) {
+int epp_active_ids(const epp_paths* p, int k, const int32_t** ids, int64_t* count) {
     if (k < 0 || k > p->L) { epp_set_error("k=%d outside [0, %d]", k, p->L); return EPP_ERR_INVALID_ARG; }
     *count = p->set_size[k];
-    if (k > 0) {  // N^k is the row set of SG_{L-k}
-        *ids = p->path[p->L - k]->row_ids.as<int32_t>();
-        return EPP_OK;
-    }
-    if (!p->have_set0_ids) {
-        HostScalars hs;
-        EPP_TRY(hs.init());
-        DevBuf tile_cnt, tile_base, dev_total;
-        const size_t tiles = std::max<size_t>(grid_for((p->n + 63) / 64, kWordsPerTile), 1);
-        EPP_TRY(tile_cnt.alloc(tiles * 4));
-        EPP_TRY(tile_base.alloc(tiles * 4));
-        EPP_TRY(dev_total.alloc(sizeof(long long)));
-        int64_t c = 0;
-        EPP_TRY(compact_bitmap(p->bitmaps[0], p->n, nullptr, 0, &p->set0_ids, nullptr, &c, tile_cnt, tile_base,
-                               dev_total, hs, s));
-        EPP_HIP_TRY(hipStreamSynchronize(s));
-        p->have_set0_ids = true;
-    }
-    *ids = p->set0_ids.as<int32_t>();
+    // N^k, k >= 1, is the row set of SG_{L-k}; N^0 was compacted when the handle was made
+    *ids = k > 0 ? p->path[p->L - k]->row_ids.as<int32_t>() : p->set0_ids.as<int32_t>();
     return EPP_OK;
 }
 

@@ -107,6 +107,8 @@ def depth_study(args):
         for l in range(L - 1, -1, -1):
             p = paths.path(l)
             x, y = _inputs(paths, g.n, F, L - l - 1, dev, cfg.seed(10 + l))
+            p.prepare_width(F)
+            full.prepare_width(F)
             a = _time_ms(lambda: epp.epp_backward_aggregate(p, x, y), reps=5)
             b = _time_ms(lambda: epp.epp_full_aggregate(full, x, y), reps=5)
             i = p.info()
@@ -228,7 +230,9 @@ def overlap_study(args):
             out.append((time.perf_counter() - t) * 1e3)
         return sorted(out)[len(out) // 2]
 
-    forward()  # schedules of the all-active graph
+    for l in range(L):
+        full.prepare_width(cfg.widths[l])  # schedules of the all-active graph
+    forward()
     side = torch.cuda.Stream()
 
     def prepare_only():
@@ -290,7 +294,7 @@ def gsfit_study(args):
                 chosen = p.select_group_size(F)
                 rec = {"study": "gsfit-sample", "graph": gi, "kind": kind, "n": n, "deg": deg, "train_frac": frac,
                        "l": l, "F": F, "rows": info.n_rows, "nnz": info.nnz, "max_len": info.max_len,
-                       "times_ms": times, "best_gs": min(times, key=times.get), "selector_gs": chosen,
+                       "len_hist": info.len_hist, "times_ms": times, "best_gs": min(times, key=times.get), "selector_gs": chosen,
                        "paper_linreg_gs": epp.epp_paper_linreg_group_size(max(info.n_rows, 1), info.nnz // 2)}
                 samples.append(rec)
                 print(json.dumps(rec), flush=True)

@@ -69,6 +69,7 @@ def run_partial(path, X: np.ndarray, poison: float | None = None) -> np.ndarray:
     d = dev()
     gin = torch.from_numpy(X).to(d)
     gout = torch.zeros_like(gin) if poison is None else torch.full_like(gin, poison)
+    path.prepare_width(gin.shape[1])  # one-off per (path, width); the aggregate call only enqueues
     epp.epp_backward_aggregate(path, gin, gout)
     torch.cuda.synchronize()
     return gout.cpu().numpy()
@@ -78,6 +79,7 @@ def run_full(full, X: np.ndarray) -> np.ndarray:
     d = dev()
     gin = torch.from_numpy(X).to(d)
     gout = torch.full_like(gin, 7.0)  # every row must be overwritten
+    full.prepare_width(gin.shape[1])
     epp.epp_full_aggregate(full, gin, gout)
     torch.cuda.synchronize()
     return gout.cpu().numpy()
@@ -88,6 +90,7 @@ def run_ifelse(full, paths, l, X: np.ndarray, poison: float = 123.0) -> np.ndarr
     d = dev()
     gin = torch.from_numpy(X).to(d)
     gout = torch.full_like(gin, poison)
+    full.prepare_width(gin.shape[1])
     epp.epp_ifelse_aggregate(full, paths, l, gin, gout)
     torch.cuda.synchronize()
     return gout.cpu().numpy()

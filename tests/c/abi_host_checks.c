@@ -19,9 +19,10 @@ int main(void) {
     epp_csr_t g;
     int32_t dummy = 0;
     float fdummy = 0.0f;
+    epp_alloc_t no_alloc = {NULL, NULL, NULL}; /* alloc == NULL: the library's own hipMalloc */
 
     CHECK(epp_last_error() != NULL);
-    CHECK(epp_prepare(NULL, NULL, 0, 2, NULL, &paths) == EPP_ERR_INVALID_ARG);
+    CHECK(epp_prepare(NULL, NULL, 0, 2, NULL, NULL, &paths) == EPP_ERR_INVALID_ARG);
     CHECK(strlen(epp_last_error()) > 0);
 
     g.n = 10;
@@ -29,18 +30,19 @@ int main(void) {
     g.rowptr = &dummy; /* never dereferenced: the calls below fail before any GPU work */
     g.col = &dummy;
     g.val = &fdummy;
-    CHECK(epp_prepare(&g, NULL, 0, 0, NULL, &paths) == EPP_ERR_INVALID_ARG);  /* L < 1 */
-    CHECK(epp_prepare(&g, NULL, 3, 2, NULL, &paths) == EPP_ERR_INVALID_ARG);  /* ids NULL */
+    CHECK(epp_prepare(&g, NULL, 0, 0, NULL, NULL, &paths) == EPP_ERR_INVALID_ARG);  /* L < 1 */
+    CHECK(epp_prepare(&g, NULL, 3, 2, NULL, NULL, &paths) == EPP_ERR_INVALID_ARG);  /* ids NULL */
     g.n = (int64_t)1 << 30;
-    CHECK(epp_prepare(&g, NULL, 0, 2, NULL, &paths) == EPP_ERR_TOO_LARGE);
-    CHECK(epp_prepare_full(&g, NULL, &full) == EPP_ERR_TOO_LARGE);
+    CHECK(epp_prepare(&g, NULL, 0, 2, &no_alloc, NULL, &paths) == EPP_ERR_TOO_LARGE);
+    CHECK(epp_prepare_full(&g, &no_alloc, NULL, &full) == EPP_ERR_TOO_LARGE);
     g.n = -1;
-    CHECK(epp_prepare_full(&g, NULL, &full) == EPP_ERR_INVALID_ARG);
+    CHECK(epp_prepare_full(&g, NULL, NULL, &full) == EPP_ERR_INVALID_ARG);
 
-    CHECK(epp_paths_import(10, 1, NULL, 0, NULL, NULL, &paths) == EPP_ERR_INVALID_ARG);
+    CHECK(epp_paths_import(10, 1, NULL, 0, NULL, NULL, NULL, &paths) == EPP_ERR_INVALID_ARG);
     CHECK(epp_num_layers(NULL) == EPP_ERR_INVALID_ARG);
     CHECK(epp_get_path(NULL, 0) == NULL);
     CHECK(epp_select_group_size(NULL, 16) == EPP_ERR_INVALID_ARG);
+    CHECK(epp_path_prepare_width(NULL, 16, NULL) == EPP_ERR_INVALID_ARG);
     CHECK(epp_backward_aggregate(NULL, &fdummy, &fdummy, 16, NULL) == EPP_ERR_INVALID_ARG);
     CHECK(epp_full_aggregate(NULL, &fdummy, &fdummy, 16, NULL) == EPP_ERR_INVALID_ARG);
     CHECK(epp_weight_gradient_workspace(NULL, 0, 16, 16) == EPP_ERR_INVALID_ARG);

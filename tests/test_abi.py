@@ -15,7 +15,8 @@ def declared_functions():
 def test_header_declares_the_documented_entry_points():
     names = declared_functions()
     for must in ("epp_prepare", "epp_backward_aggregate", "epp_full_aggregate", "epp_prepare_full",
-                 "epp_path_export", "epp_active_set_export", "epp_select_group_size", "epp_last_error"):
+                 "epp_path_export", "epp_active_set_export", "epp_select_group_size", "epp_last_error",
+                 "epp_path_prepare_width"):
         assert must in names
 
 
@@ -36,22 +37,23 @@ def test_host_side_argument_checks_need_no_gpu():
     assert lib.epp_num_layers(None) == epp.EPP_ERR_INVALID_ARG
     assert b"NULL" in lib.epp_last_error()
     out = ctypes.c_void_p()
-    assert lib.epp_prepare(None, None, 0, 1, None, ctypes.byref(out)) == epp.EPP_ERR_INVALID_ARG
+    assert lib.epp_prepare(None, None, 0, 1, None, None, ctypes.byref(out)) == epp.EPP_ERR_INVALID_ARG
     assert lib.epp_select_group_size(None, 16) == epp.EPP_ERR_INVALID_ARG
+    assert lib.epp_path_prepare_width(None, 16, None) == epp.EPP_ERR_INVALID_ARG
     # size limits are checked before anything is dereferenced or sent to the GPU
     dummy = ctypes.c_void_p(16)
     for n, nnz, want in ((1 << 30, 10, epp.EPP_ERR_TOO_LARGE), (10, (1 << 31) - 1, epp.EPP_ERR_TOO_LARGE),
                          (-1, 0, epp.EPP_ERR_INVALID_ARG)):
         csr = epp._Csr(n, nnz, dummy, dummy, dummy)
-        assert lib.epp_prepare(ctypes.byref(csr), None, 0, 2, None, ctypes.byref(out)) == want
-        assert lib.epp_prepare_full(ctypes.byref(csr), None, ctypes.byref(out)) == want
+        assert lib.epp_prepare(ctypes.byref(csr), None, 0, 2, None, None, ctypes.byref(out)) == want
+        assert lib.epp_prepare_full(ctypes.byref(csr), None, None, ctypes.byref(out)) == want
     # combination stage: NULL handles and NULL matrices are refused on the host
     assert lib.epp_weight_gradient_workspace(None, 0, 16, 16) == epp.EPP_ERR_INVALID_ARG
     assert lib.epp_weight_gradient(None, 0, dummy, 16, dummy, 16, dummy, dummy, 1 << 20, None) == epp.EPP_ERR_INVALID_ARG
     assert lib.epp_input_gradient(None, 0, dummy, 16, dummy, 16, dummy, None) == epp.EPP_ERR_INVALID_ARG
     csr = epp._Csr(10, 10, dummy, dummy, dummy)
-    assert lib.epp_prepare(ctypes.byref(csr), None, 0, 0, None, ctypes.byref(out)) == epp.EPP_ERR_INVALID_ARG  # L < 1
-    assert lib.epp_prepare(ctypes.byref(csr), None, 5, 1, None, ctypes.byref(out)) == epp.EPP_ERR_INVALID_ARG  # ids NULL
+    assert lib.epp_prepare(ctypes.byref(csr), None, 0, 0, None, None, ctypes.byref(out)) == epp.EPP_ERR_INVALID_ARG  # L < 1
+    assert lib.epp_prepare(ctypes.byref(csr), None, 5, 1, None, None, ctypes.byref(out)) == epp.EPP_ERR_INVALID_ARG  # ids NULL
 
 
 def test_paper_linear_regression_group_size():

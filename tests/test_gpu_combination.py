@@ -184,7 +184,7 @@ def test_combination_at_benchmark_sizes(cfg_id):
 
 def test_backward_epoch_in_a_hip_graph():
     """Combination and aggregation of every layer, chained as in Alg. 1's backward loop, captured
-    once in a HIP graph (after a first eager epoch that builds schedules and the id list of N^0)
+    once in a HIP graph (after the widths have been prepared and a first eager epoch has run)
     and replayed with eager work in between: every replay must equal the eager epoch bit for bit
     on the weight gradients (fixed summation order) and within tolerance of the oracle chain."""
     g = graphgen.random_graph("chung_lu", 6000, seed=460, target_edges=30_000)
@@ -203,6 +203,8 @@ def test_backward_epoch_in_a_hip_graph():
     wss = [torch.empty(epp.epp_weight_gradient_workspace(paths, L - l - 1, widths[l], widths[l + 1]),
                        dtype=torch.uint8, device=d) for l in range(L)]
     ps = [paths.path(l) for l in range(L)]
+    for l in range(L):
+        ps[l].prepare_width(widths[l])
 
     def epoch():
         for l in range(L - 1, -1, -1):

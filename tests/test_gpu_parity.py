@@ -180,10 +180,35 @@ def test_error_paths():
     assert e.value.code == epp.EPP_ERR_INVALID_ARG
     paths = gpu_prepare(g, [1], 1)
     x = torch.zeros(10, 4, device=dev())
+    with pytest.raises(epp.EppError) as e:
+        epp.epp_backward_aggregate(paths.path(0), x, torch.zeros_like(x))  # width 4 not prepared
+    assert e.value.code == epp.EPP_ERR_INVALID_ARG and "prepare_width" in str(e.value)
+    paths.path(0).prepare_width(4)
+    epp.epp_backward_aggregate(paths.path(0), x, torch.zeros_like(x))
     with pytest.raises(epp.EppError):
         epp.epp_full_aggregate(paths.path(0), x, torch.zeros_like(x))  # not an all-active handle
     with pytest.raises(epp.EppError):
         epp.epp_backward_aggregate(paths.path(0), x, x)  # aliasing
+    with pytest.raises(ValueError):
+        epp.epp_backward_aggregate(paths.path(0), x[:9], torch.zeros_like(x[:9]))  # fewer rows than vertices
+    # the caller's CSR is checked on the GPU before it is used as an index
+    d = dev()
+    rowptr, col, val = (torch.from_numpy(a).to(d) for a in (g.rowptr, g.col, g.val))
+    ids = torch.tensor([1], dtype=torch.int32, device=d)
+    for bad_col in (-1, 10, 2 ** 30):
+        c = col.clone()
+        c[3] = bad_col
+        for call in (lambda: epp.epp_prepare(g.n, rowptr, c, val, ids, 2), lambda: epp.epp_prepare_full(g.n, rowptr, c, val)):
+            with pytest.raises(epp.EppError) as e:
+                call()
+            assert e.value.code == epp.EPP_ERR_OUT_OF_RANGE_ID
+    for pos, bad_ptr in ((0, 1), (4, 0), (4, g.nnz + 5), (g.n, g.nnz - 1)):
+        r = rowptr.clone()
+        r[pos] = bad_ptr
+        for call in (lambda: epp.epp_prepare(g.n, r, col, val, ids, 2), lambda: epp.epp_prepare_full(g.n, r, col, val)):
+            with pytest.raises(epp.EppError) as e:
+                call()
+            assert e.value.code == epp.EPP_ERR_INVALID_ARG, (pos, bad_ptr)
 
 
 def test_run_to_run_determinism_of_every_row():
@@ -262,6 +287,114 @@ def test_export_is_unchanged_by_aggregation_and_hot_cold_marking(monkeypatch):
         assert_paths_bit_exact(paths, sets_o, paths_o, 2)
 
 
+@pytest.mark.parametrize("F", [128, 130, 256])
+@pytest.mark.parametrize("slices", ["1", "2", "3"])
+@pytest.mark.parametrize("hot_mb", ["0", "1"])
+def test_xcd_feature_slices_and_cold_marks_on_every_row(monkeypatch, F, slices, hot_mb):
+    """The XCD feature-slicing launch shapes (2, 4 and 8 slices, whatever the library would pick
+    by itself) with and without streamed (cold) sources, on a path whose rows are cut by many
+    group boundaries: every row against the oracle, NaN poison outside the source set included."""
+    g = graphgen.random_graph("rmat", 30_000, seed=171, raw_draws=400_000)
+    train = graphgen.training_set(g.n, 3000, 172)
+    sets_o, paths_o = oprep(g, train, 2)
+    monkeypatch.setenv("EPP_TUNE_LOG2_SLICES", slices)
+    monkeypatch.setenv("EPP_TUNE_HOT_MB", hot_mb)
+    paths = gpu_prepare(g, train, 2)
+    for l, gs in ((0, 24), (1, 0)):
+        X = graphgen.normal_rows(g.n, F, sets_o[2 - l - 1], 173 + l)
+        want = oracle.path_aggregate(g.n, paths_o[l], X)
+        p = paths.path(l)
+        if gs:
+            p.set_group_size(F, gs)
+            assert p.info().n_split_rows > 1000
+        rows = sets_o[2 - l].astype(bool)
+        got = run_partial(p, X, poison=9.0)
+        assert np.all(got[~rows] == 9.0)
+        assert_close(got[rows], want[rows], f"slices 2^{slices} hot {hot_mb} MB F={F} l={l}")
+        Xp = X.copy()
+        Xp[sets_o[2 - l - 1] == 0] = np.nan
+        assert_close(run_partial(p, Xp), want, f"slices 2^{slices} hot {hot_mb} MB F={F} l={l}, nan-poison")
+
+
+def test_marks_of_a_path_do_not_depend_on_the_order_of_its_widths(monkeypatch):
+    """One path used at two widths: the streamed-source marks are those of the wider width,
+    whichever was prepared first, and results stay within tolerance either way."""
+    g = graphgen.random_graph("rmat", 30_000, seed=71, raw_draws=400_000)
+    train = graphgen.training_set(g.n, 3000, 72)
+    sets_o, paths_o = oprep(g, train, 2)
+    monkeypatch.setenv("EPP_TUNE_HOT_MB", "1")
+    outs = []
+    for order in ((64, 128), (128, 64)):
+        paths = gpu_prepare(g, train, 2)
+        p = paths.path(0)
+        for F in order:
+            p.prepare_width(F)
+        res = {}
+        for F in (64, 128):
+            X = graphgen.normal_rows(g.n, F, sets_o[1], 75)
+            res[F] = run_partial(p, X)
+            assert_close(res[F], oracle.path_aggregate(g.n, paths_o[0], X), f"order {order} F={F}")
+        outs.append(res)
+        assert_paths_bit_exact(paths, sets_o, paths_o, 2)
+    for F in (64, 128):  # same marks, same schedule, same summation order
+        assert np.array_equal(outs[0][F], outs[1][F])
+
+
+def test_caller_allocator_owns_every_byte_and_aggregation_never_allocates():
+    """With the PyTorch-backed epp_alloc_t every device buffer of the handles is a block of
+    PyTorch's caching allocator: preparing allocates through it, the aggregate calls allocate
+    nothing at all (neither through it nor behind its back), destroying the handles gives every
+    block back.  Without it the library falls back to hipMalloc and PyTorch sees none of it."""
+    import gc
+
+    g = graphgen.random_graph("rmat", 20_000, seed=61, raw_draws=300_000)
+    train = graphgen.training_set(g.n, 2000, 62)
+    sets_o, paths_o = oprep(g, train, 2)
+    d = dev()
+    rowptr, col, val = (torch.from_numpy(a).to(d) for a in (g.rowptr, g.col, g.val))
+    ids = torch.from_numpy(np.ascontiguousarray(train, np.int32)).to(d)
+    F = 32
+    X = graphgen.normal_rows(g.n, F, sets_o[1], 63)
+    gin = torch.from_numpy(X).to(d)
+    gout = torch.zeros_like(gin)
+    want = oracle.path_aggregate(g.n, paths_o[0], X)
+    gc.collect()
+    torch.cuda.synchronize()
+    for use_torch in (True, False):
+        live0, allocs0 = epp.alloc_stats["live"], epp.alloc_stats["allocs"]
+        mem0 = torch.cuda.memory_allocated()
+        free0 = torch.cuda.mem_get_info()[0]
+        paths = epp.epp_prepare(g.n, rowptr, col, val, ids, 2, torch_allocator=use_torch)
+        full = epp.epp_prepare_full(g.n, rowptr, col, val, torch_allocator=use_torch)
+        p = paths.path(0)
+        p.set_group_size(F, 16)  # cut rows: partial rows are allocated too
+        full.prepare_width(F)
+        torch.cuda.synchronize()
+        held = p.info().bytes + full.info().bytes
+        if use_torch:
+            assert epp.alloc_stats["allocs"] > allocs0 and epp.alloc_stats["live"] > live0
+            assert torch.cuda.memory_allocated() - mem0 >= held  # PyTorch accounts for every byte held
+        else:
+            assert epp.alloc_stats["allocs"] == allocs0
+            assert torch.cuda.memory_allocated() == mem0
+        # the aggregate calls: no allocation of any kind, no change of the device's free memory
+        a1, m1, f1 = epp.alloc_stats["allocs"], torch.cuda.memory_allocated(), torch.cuda.mem_get_info()[0]
+        for _ in range(3):
+            epp.epp_backward_aggregate(p, gin, gout)
+            epp.epp_full_aggregate(full, gin, gout)
+            epp.epp_ifelse_aggregate(full, paths, 0, gin, gout)
+            gout.zero_()
+            epp.epp_backward_aggregate(p, gin, gout)
+        assert (epp.alloc_stats["allocs"], torch.cuda.memory_allocated(), torch.cuda.mem_get_info()[0]) == (a1, m1, f1)
+        torch.cuda.synchronize()
+        assert_close(gout.cpu().numpy(), want, f"torch allocator {use_torch}")
+        del p, paths, full
+        gc.collect()
+        assert epp.alloc_stats["live"] == live0
+        assert torch.cuda.memory_allocated() == mem0
+        del free0
+
+
 def test_deep_model_shares_the_saturated_path():
     """Once N^{k+1} == N^k every deeper layer has the same execution path: it is built once."""
     n = 40
@@ -279,9 +412,10 @@ def test_deep_model_shares_the_saturated_path():
 
 
 def test_epoch_captured_in_a_hip_graph_replays_correctly():
-    """After the first (schedule-building) call the aggregate entry points only enqueue
-    kernels, so a whole epoch can be captured in a HIP graph; every replay must reproduce the
-    eager result (split rows are re-zeroed by a kernel inside the graph)."""
+    """The aggregate entry points only enqueue kernels (the one-off work of a width is done by
+    epp_path_prepare_width), so a whole epoch can be captured in a HIP graph without any eager
+    call before it; every replay must reproduce the oracle's result (rows cut by group
+    boundaries are summed from per-group partial rows by a second kernel inside the graph)."""
     cfg = graphgen.make_config(1)
     g, L = cfg.graph, cfg.L
     sets_o, paths_o = oprep(g, cfg.train_ids, L)
@@ -296,7 +430,8 @@ def test_epoch_captured_in_a_hip_graph_replays_correctly():
         for l in range(L - 1, -1, -1):
             epp.epp_backward_aggregate(ps[l], xs[l], ys[l])
 
-    epoch()  # builds the schedules (allocates, synchronises): must happen before capture
+    for l in range(L):
+        ps[l].prepare_width(xs[l].shape[1])  # allocates, synchronises: must happen before capture
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):

@@ -333,3 +333,23 @@ def test_generator_invariants():
     assert len(set(t.tolist())) == 100
     tb = graphgen.training_set(3000, 100, 1, deg)
     assert len(set(tb.tolist())) == 100 and deg[tb].mean() > deg.mean()
+
+
+def test_strided_row_sample_equals_the_full_result_on_the_sampled_rows():
+    """oracle.path_aggregate(first, stride) is what the benchmark's cpu_baseline times: it must
+    compute exactly the rows first, first + stride, ... of the full result and leave all others zero."""
+    g = graphgen.random_graph("rmat", 3000, seed=5, raw_draws=40_000)
+    train = graphgen.training_set(g.n, 200, 6)
+    sets, paths = oracle.prepare(g.n, g.rowptr, g.col, g.val, train, 2)
+    for l in range(2):
+        X = graphgen.normal_rows(g.n, 5, sets[2 - l - 1], 7 + l)
+        full = oracle.path_aggregate(g.n, paths[l], X)  # (pinned by the dense products above)
+        assert full[paths[l].row_ids].any()
+        R = paths[l].row_ids.size
+        for first, stride in ((0, 1), (0, 7), (3, 7), (6, 7), (R - 1, R), (0, R + 5), (R, 3)):
+            part = oracle.path_aggregate(g.n, paths[l], X, first=first, stride=stride)
+            picked = paths[l].row_ids[first::stride]
+            mask = np.zeros(g.n, bool)
+            mask[picked] = True
+            assert np.array_equal(part[mask], full[mask]), (l, first, stride)
+            assert not part[~mask].any(), (l, first, stride)
