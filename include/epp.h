@@ -227,6 +227,22 @@ int epp_weight_gradient(epp_paths_t* paths, int k, const float* Y, int F_in, con
 int epp_input_gradient(epp_paths_t* paths, int k, const float* grad_X, int F_out, const float* W, int F_in,
                        float* grad_Y, epp_stream_t stream);
 
+/* epp_weight_gradient for callers that cannot allocate device memory and have no workspace to pass:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments and result as epp_weight_gradient (to the same tolerance: the partial sums may be cut
+ * at other rows), minus the workspace: the partial sums live in a 32 MiB device array that is part
+ * of the library's code object (every GPU the library runs on holds its own copy until the process
+ * ends).  The call allocates nothing, on the device or through any library, and only enqueues
+ * kernels on `stream`.
+ *   limit   F_in * F_out <= 8,388,608 (one block of partial sums must fit the array); beyond it
+ *           EPP_ERR_TOO_LARGE, and epp_weight_gradient with a workspace is the way.  Wide matrices
+ *           get fewer blocks of rows (32 MiB / (4 F_in F_out)), hence less parallelism.
+ *   sharing every call on one GPU uses that GPU's one array: calls that can overlap in time on one
+ *           GPU (different streams, different host threads) race on it and must be serialised by
+ *           the caller.  Nothing in the array has to be zero; a call writes every word it later reads. */
+int epp_weight_gradient_static(epp_paths_t* paths, int k, const float* Y, int F_in, const float* grad_X, int F_out,
+                               float* grad_W, epp_stream_t stream);
+
 void epp_destroy_paths(epp_paths_t* p);
 void epp_destroy_path(epp_path_t* p); /* only for handles from epp_prepare_full */
 

@@ -28,7 +28,7 @@ EXPORTED = [
     "epp_backward_aggregate", "epp_full_aggregate", "epp_destroy_paths", "epp_destroy_path",
     "epp_last_error", "epp_paper_linreg_group_size", "epp_ifelse_aggregate",
     "epp_weight_gradient_workspace", "epp_weight_gradient", "epp_input_gradient", "epp_paths_import",
-    "epp_path_prepare_width",
+    "epp_path_prepare_width", "epp_weight_gradient_static",
 ]
 
 
@@ -125,6 +125,7 @@ def load_library() -> ctypes.CDLL:
     lib.epp_weight_gradient_workspace.argtypes = [P, I, I, I]
     lib.epp_weight_gradient_workspace.restype = I64
     lib.epp_weight_gradient.argtypes = [P, I, P, I, P, I, P, P, I64, P]
+    lib.epp_weight_gradient_static.argtypes = [P, I, P, I, P, I, P, P]
     lib.epp_input_gradient.argtypes = [P, I, P, I, P, I, P, P]
     lib.epp_paths_import.argtypes = [I64, I, P, I64, ctypes.POINTER(_PathArrays), A, P, ctypes.POINTER(P)]
     lib.epp_destroy_paths.argtypes = [P]
@@ -337,6 +338,17 @@ def epp_weight_gradient(paths: Paths, k: int, Y: torch.Tensor, grad_X: torch.Ten
         raise ValueError("workspace must be a contiguous CUDA uint8 tensor")
     _check(load_library().epp_weight_gradient(paths._h, k, Y.data_ptr(), Y.shape[1], grad_X.data_ptr(), grad_X.shape[1],
                                               grad_W.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()))
+
+
+def epp_weight_gradient_static(paths: Paths, k: int, Y: torch.Tensor, grad_X: torch.Tensor,
+                               grad_W: torch.Tensor) -> None:
+    """epp_weight_gradient without a workspace: the partial sums use the library's static device array
+    (no allocation anywhere; F_in * F_out <= 8,388,608; calls on one GPU must not overlap)."""
+    _matrix(Y, "Y"), _matrix(grad_X, "grad_X"), _matrix(grad_W, "grad_W")
+    if Y.shape[0] != paths.n or grad_X.shape[0] != paths.n or grad_W.shape != (Y.shape[1], grad_X.shape[1]):
+        raise ValueError("shapes: Y n x F_in, grad_X n x F_out, grad_W F_in x F_out")
+    _check(load_library().epp_weight_gradient_static(paths._h, k, Y.data_ptr(), Y.shape[1], grad_X.data_ptr(),
+                                                     grad_X.shape[1], grad_W.data_ptr(), _stream()))
 
 
 def epp_input_gradient(paths: Paths, k: int, grad_X: torch.Tensor, W: torch.Tensor, grad_Y: torch.Tensor) -> None:

@@ -28,6 +28,7 @@ constexpr int kBlock = 256;
 constexpr int kStep = 32;   // contraction step
 constexpr int kMaxWidth = 4096;
 constexpr int kMinChunkRows = 256;
+constexpr int64_t kNoChunkLimit = (int64_t)1 << 40;
 
 typedef float float4v __attribute__((ext_vector_type(4)));
 
@@ -264,12 +265,13 @@ int row_set(const epp_paths* p, int k, const int32_t** ids, int64_t* count) {
     return epp_active_ids(p, k, ids, count);
 }
 
-// Rows per partial sum: enough chunks to fill the chip a few times over, whole steps each.
-void chunking(int64_t n_rows, int Fi, int Fo, int64_t* rows_per_chunk, int64_t* n_chunks) {
+// Rows per partial sum: enough chunks to fill the chip a few times over (at most `max_chunks`
+// of them), whole steps each.
+void chunking(int64_t n_rows, int Fi, int Fo, int64_t max_chunks, int64_t* rows_per_chunk, int64_t* n_chunks) {
     int tm, tn;
     tile_dims(tile_shape(Fi, Fo), &tm, &tn);
     const int64_t tiles = (int64_t)((Fi + tm - 1) / tm) * ((Fo + tn - 1) / tn);
-    const int64_t want = std::max<int64_t>(1, 2048 / tiles);
+    const int64_t want = std::min(std::max<int64_t>(1, 2048 / tiles), std::max<int64_t>(max_chunks, 1));
     int64_t per = std::max<int64_t>((n_rows + want - 1) / want, kMinChunkRows);
     per = (per + kStep - 1) / kStep * kStep;
     *rows_per_chunk = per;
@@ -283,32 +285,26 @@ extern "C" int64_t epp_weight_gradient_workspace(const epp_paths_t* paths, int k
     if (k < -1 || k > paths->L) { epp_set_error("k=%d outside [-1, %d]", k, paths->L); return EPP_ERR_INVALID_ARG; }
     if (check_widths(F_in, F_out) != EPP_OK) return EPP_ERR_INVALID_ARG;
     int64_t per, chunks;
-    chunking(k < 0 ? paths->n : paths->set_size[k], F_in, F_out, &per, &chunks);
+    chunking(k < 0 ? paths->n : paths->set_size[k], F_in, F_out, kNoChunkLimit, &per, &chunks);
     return std::max<int64_t>(chunks, 1) * F_in * F_out * (int64_t)sizeof(float);
 }
 
-extern "C" int epp_weight_gradient(epp_paths_t* paths, int k, const float* Y, int F_in, const float* grad_X, int F_out,
-                                   float* grad_W, void* workspace, int64_t workspace_bytes, epp_stream_t stream) {
-    if (!paths || !Y || !grad_X || !grad_W || !workspace) { epp_set_error("NULL argument"); return EPP_ERR_INVALID_ARG; }
-    if (k < -1 || k > paths->L) { epp_set_error("k=%d outside [-1, %d]", k, paths->L); return EPP_ERR_INVALID_ARG; }
-    EPP_TRY(check_widths(F_in, F_out));
-    const int64_t need = epp_weight_gradient_workspace(paths, k, F_in, F_out);
-    if (workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 15)) {
-        epp_set_error("workspace of %lld bytes (need %lld, 16-byte aligned)", (long long)workspace_bytes, (long long)need);
-        return EPP_ERR_INVALID_ARG;
-    }
-    hipStream_t s = (hipStream_t)stream;
+namespace {
+
+// Both weight-gradient entry points: partial sums of at most `max_chunks` blocks of rows go to
+// `part` (max_chunks * F_in * F_out floats at least), a second kernel adds them in a fixed order.
+int weight_gradient(const epp_paths* paths, int k, const float* Y, int F_in, const float* grad_X, int F_out,
+                    float* grad_W, float* part, int64_t max_chunks, hipStream_t s) {
     const int32_t* ids = nullptr;
     int64_t n_rows = 0;
     EPP_TRY(row_set(paths, k, &ids, &n_rows));
     int64_t per, chunks;
-    chunking(n_rows, F_in, F_out, &per, &chunks);
+    chunking(n_rows, F_in, F_out, max_chunks, &per, &chunks);
     if (chunks > 0) {
         const TileShape shape = tile_shape(F_in, F_out);
         int tm, tn;
         tile_dims(shape, &tm, &tn);
         const dim3 grid((unsigned)chunks, (unsigned)((F_in + tm - 1) / tm), (unsigned)((F_out + tn - 1) / tn));
-        float* part = static_cast<float*>(workspace);
         const bool vec = aligned4(F_in, F_out, Y, grad_X);
 #define EPP_LAUNCH_WG(WM, WN, BM, BN)                                                                            \
     do {                                                                                                         \
@@ -331,9 +327,74 @@ extern "C" int epp_weight_gradient(epp_paths_t* paths, int k, const float* Y, in
     }
     const int64_t total = (int64_t)F_in * F_out;
     hipLaunchKernelGGL(k_weight_gradient_reduce, dim3((unsigned)((total + 15) / 16)), dim3(kBlock), 0, s,
-                       static_cast<const float*>(workspace), chunks, total, grad_W);
+                       static_cast<const float*>(part), chunks, total, grad_W);
     EPP_HIP_TRY(hipGetLastError());
     return EPP_OK;
+}
+
+}  // namespace
+
+extern "C" int epp_weight_gradient(epp_paths_t* paths, int k, const float* Y, int F_in, const float* grad_X, int F_out,
+                                   float* grad_W, void* workspace, int64_t workspace_bytes, epp_stream_t stream) {
+    if (!paths || !Y || !grad_X || !grad_W || !workspace) { epp_set_error("NULL argument"); return EPP_ERR_INVALID_ARG; }
+    if (k < -1 || k > paths->L) { epp_set_error("k=%d outside [-1, %d]", k, paths->L); return EPP_ERR_INVALID_ARG; }
+    EPP_TRY(check_widths(F_in, F_out));
+    const int64_t need = epp_weight_gradient_workspace(paths, k, F_in, F_out);
+    if (workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 15)) {
+        epp_set_error("workspace of %lld bytes (need %lld, 16-byte aligned)", (long long)workspace_bytes, (long long)need);
+        return EPP_ERR_INVALID_ARG;
+    }
+    return weight_gradient(paths, k, Y, F_in, grad_X, F_out, grad_W, static_cast<float*>(workspace), kNoChunkLimit,
+                           (hipStream_t)stream);
+}
+
+// ---- the entry point that allocates nothing --------------------------------------------------
+// Partial sums of epp_weight_gradient_static: a file-scope device array instead of a caller's
+// workspace.  Every GPU the library runs on holds its own copy until the process ends.  In host
+// code the array's name is only a handle for the symbol lookup; the device address of the current
+// GPU's copy comes from hipGetSymbolAddress, once per device, and is what the kernels receive.
+constexpr size_t kStaticScratchBytes = 32u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+float* g_scratch_ptr[kMaxDevices] = {};  // per device; written once (the same value by any thread that races)
+}  // namespace
+
+int epp_static_scratch(float** ptr) {
+    int dev = -1;
+    EPP_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) { epp_set_error("device index %d not supported", dev); return EPP_ERR_INVALID_ARG; }
+    float* p = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+    if (!p) {
+        void* addr = nullptr;
+        EPP_HIP_TRY(hipGetSymbolAddress(&addr, HIP_SYMBOL(scratch)));
+        if (!addr) { epp_set_error("the static scratch array has no device address"); return EPP_ERR_HIP; }
+        p = static_cast<float*>(addr);
+        __atomic_store_n(&g_scratch_ptr[dev], p, __ATOMIC_RELEASE);
+    }
+    *ptr = p;
+    return EPP_OK;
+}
+
+extern "C" int epp_weight_gradient_static(epp_paths_t* paths, int k, const float* Y, int F_in, const float* grad_X,
+                                          int F_out, float* grad_W, epp_stream_t stream) {
+    if (!paths || !Y || !grad_X || !grad_W) { epp_set_error("NULL argument"); return EPP_ERR_INVALID_ARG; }
+    if (k < -1 || k > paths->L) { epp_set_error("k=%d outside [-1, %d]", k, paths->L); return EPP_ERR_INVALID_ARG; }
+    EPP_TRY(check_widths(F_in, F_out));
+    const int64_t block_bytes = (int64_t)F_in * F_out * (int64_t)sizeof(float);
+    if (block_bytes > (int64_t)kStaticScratchBytes) {
+        epp_set_error("F_in * F_out = %lld exceeds the %lld elements the static scratch array holds; use "
+                      "epp_weight_gradient with a workspace", (long long)F_in * F_out,
+                      (long long)(kStaticScratchBytes / sizeof(float)));
+        return EPP_ERR_TOO_LARGE;
+    }
+    float* part = nullptr;
+    EPP_TRY(epp_static_scratch(&part));
+    // as many blocks of rows as fit the array; every block is written in full before the second
+    // kernel reads it, so nothing left over from an earlier call is ever read
+    return weight_gradient(paths, k, Y, F_in, grad_X, F_out, grad_W, part, (int64_t)kStaticScratchBytes / block_bytes,
+                           (hipStream_t)stream);
 }
 
 extern "C" int epp_input_gradient(epp_paths_t* paths, int k, const float* grad_X, int F_out, const float* W, int F_in,

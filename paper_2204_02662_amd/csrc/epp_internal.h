@@ -199,6 +199,11 @@ void epp_path_set_stats(epp_path* p, const unsigned long long* host);
 // ascending vertex ids of N^k (device, owned by `p`); allocates nothing, never waits
 int epp_active_ids(const epp_paths* p, int k, const int32_t** ids, int64_t* count);
 
+// combine.hip
+// device address of the static scratch array on the current GPU (symbol lookup once per device;
+// no allocation).  Handles are created with the GPU current, so they resolve it up front.
+int epp_static_scratch(float** ptr);
+
 // aggregate.hip
 int epp_build_schedule(epp_path* p, int gs, hipStream_t s, Schedule** out);
 int epp_launch_aggregate(epp_path* p, Schedule* sc, int log2_slices, const float* in, float* out, int F, hipStream_t s,

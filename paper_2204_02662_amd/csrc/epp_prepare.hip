@@ -554,6 +554,10 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
     if (L < 1) { epp_set_error("L must be >= 1 (got %d)", L); return EPP_ERR_INVALID_ARG; }
     if (n_train < 0 || (n_train > 0 && !train_ids)) { epp_set_error("bad training set"); return EPP_ERR_INVALID_ARG; }
     hipStream_t s = (hipStream_t)stream;
+    {   // set-up of this GPU's static scratch array (used by epp_weight_gradient_static)
+        float* unused = nullptr;
+        EPP_TRY(epp_static_scratch(&unused));
+    }
     const int64_t n = g->n, nnz = g->nnz;
     const int64_t n_words = (n + 63) / 64;
     const int64_t n_seg = (nnz + 63) / 64;
@@ -816,6 +820,10 @@ extern "C" int epp_paths_import(int64_t n, int L, const int32_t* train_ids, int6
         if (a.nnz >= 0x7FFFFFFFll) { epp_set_error("layer %d: nnz=%lld (limit 2^31-1)", l, (long long)a.nnz); return EPP_ERR_TOO_LARGE; }
     }
     hipStream_t s = (hipStream_t)stream;
+    {   // set-up of this GPU's static scratch array (used by epp_weight_gradient_static)
+        float* unused = nullptr;
+        EPP_TRY(epp_static_scratch(&unused));
+    }
     const int64_t n_words = (n + 63) / 64;
     HostScalars hs;
     EPP_TRY(hs.init());
