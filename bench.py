@@ -3,16 +3,18 @@
 
 A "step" is one epoch of backward aggregation: one launch of the partially-active kernel
 per layer, l = L-1 ... 0 (Alg. 2), over synthetic inputs that are already resident in HBM.
-Prints ONE JSON line: metric/value/unit (ms per epoch of the partially-active path), per-layer
-times with algorithmic bytes and roofline fractions, the dominant kernel's `roofline` object,
-the all-active and if-else comparisons, the one-off `prepare_ms`, and `cpu_baseline` (the CPU
-oracle timed on this machine's host cores).
+Prints ONE JSON line: metric/value/unit (ms per epoch of the partially-active path on the
+headline workload), per-layer times with algorithmic bytes and roofline fractions, the
+dominant kernel's `roofline` object, the all-active and if-else comparisons, the one-off
+`prepare_ms`, the other benchmark configurations in compact form (`configs`), and
+`cpu_baseline` (the CPU oracle timed on this machine's host cores).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--only] [--no-cpu-baseline]
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -24,6 +26,10 @@ if str(ROOT) not in sys.path:
     sys.path.insert(0, str(ROOT))
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+# the chip's own random-row gather rates (profiles/gather_rate_microbenchmark.md): lines of 128 bytes per
+# second served by an XCD's L2 / from beyond it (memory-side cache or HBM alike)
+GATHER_L2_LINES_PER_S = 235e9
+GATHER_MISS_LINES_PER_S = 60e9
 
 
 def log(*a):
@@ -41,16 +47,33 @@ def edge_bytes(R: int, nnz: int, F: int) -> int:
     return 4 * (2 * R + 1) + 8 * nnz + 4 * F * nnz + 4 * F * R
 
 
+def kernel_source_hash() -> str:
+    """Hash of the HIP sources the library is built from: counter summaries are stamped with it."""
+    h = hashlib.sha256()
+    for f in sorted((ROOT / "paper_2204_02662_amd" / "csrc").glob("*")):
+        h.update(f.name.encode())
+        h.update(f.read_bytes())
+    return h.hexdigest()[:16]
+
+
 def read_traffic(workload: str):
     """(HBM bytes per launch, L2 hit rate) of the aggregation kernel per layer, from the committed rocprofv3
-    counter summary (profiles/hbm_traffic.txt: lines `<workload> <layer> <fetch_bytes> <write_bytes> <l2 hit rate>`)."""
+    counter summary profiles/hbm_traffic.txt (lines `<workload> <layer> <fetch_bytes> <write_bytes> <l2 hit rate>`
+    after a line `sources <hash>`).  The counters describe the kernels they were measured on: if the sources
+    have changed since, nothing is returned (and the bench line carries traffic = null)."""
     f = ROOT / "profiles" / "hbm_traffic.txt"
-    out = {}
+    out, stamp = {}, None
     if f.exists():
         for line in f.read_text().splitlines():
             parts = line.split()
-            if len(parts) >= 4 and parts[0] == workload:
+            if len(parts) == 2 and parts[0] == "sources":
+                stamp = parts[1]
+            elif len(parts) >= 4 and parts[0] == workload:
                 out[int(parts[1])] = (float(parts[2]) + float(parts[3]), float(parts[4]) if len(parts) > 4 else None)
+    if out and stamp != kernel_source_hash():
+        log(f"profiles/hbm_traffic.txt was measured on sources {stamp}, the library is built from "
+            f"{kernel_source_hash()}: counter-based fields (traffic, L2 hit rate) are reported as null")
+        return {}
     return out
 
 
@@ -118,40 +141,19 @@ def cpu_baseline(cfg, budget_s: float):
     return out
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=int(os.environ.get("EPP_BENCH_CONFIG", "5")))
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-all-active", action="store_true")
-    ap.add_argument("--no-combination", action="store_true", help="skip the combination-stage report")
-    ap.add_argument("--cold", action="store_true",
-                    help="also time the epoch with 1 GiB streamed through the caches before every layer launch")
-    ap.add_argument("--cpu-budget-s", type=float, default=15.0)
-    ap.add_argument("--layers", type=str, default="", help="comma list of layers to run (profiling); default all")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one plain 1 GiB device copy (reference point for the HBM byte counters)")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU only (the path has no multi-GPU part); "
-              "use --gpus 1", file=sys.stderr)
-        sys.exit(2)
-
+def run_config(config_id: int, args, detail: bool):
+    """One benchmark configuration: generate, prepare, time the partially-active epoch, the all-active
+    and if-else baselines.  `detail` adds what only the headline workload reports (combination stage,
+    flushed caches, per-epoch clearing of the output, counters).  Returns (result dict, cfg)."""
     import numpy as np
     import torch
 
     import graphgen
     import paper_2204_02662_amd as epp
 
-    epp.load_library()  # fails loudly if the HIP library is missing
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
     dev = torch.device("cuda", 0)
-
     t0 = time.perf_counter()
-    cfg = graphgen.make_config(args.config)
+    cfg = graphgen.make_config(config_id)
     g, L = cfg.graph, cfg.L
     log(f"{cfg.name}: n={g.n} nnz={g.nnz} L={L} widths(l=0..)={cfg.widths} |V_t|={cfg.n_train} "
         f"generated in {time.perf_counter() - t0:.1f}s")
@@ -189,7 +191,7 @@ def main():
     del rowptr, col, val
 
     order = [l for l in range(L - 1, -1, -1) if not args.layers or str(l) in args.layers.split(",")]
-    if args.calibrate_copy:
+    if args.calibrate_copy and detail:
         a = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         b = torch.empty_like(a)
         b.copy_(a)  # 1 GiB read + 1 GiB written by one elementwise kernel
@@ -199,6 +201,8 @@ def main():
     path_objs = [paths.path(l) for l in range(L)]
 
     def timed(run_layer, steps, warmup, between=None):
+        """HIP events on the stream the kernels are launched on (PyTorch's current stream), one pair
+        per layer launch; returns (wall ms per epoch, mean ms per layer) and leaves median/min in .spread."""
         for _ in range(warmup):
             for l in order:
                 run_layer(l)
@@ -209,7 +213,7 @@ def main():
         for s in range(steps):
             for i, l in enumerate(order):
                 if between is not None:
-                    between()  # outside the event pair
+                    between(l)  # outside the event pair
                 ev[s][i][0].record()
                 run_layer(l)
                 ev[s][i][1].record()
@@ -228,8 +232,8 @@ def main():
     torch.cuda.synchronize()
     schedule_ms = (time.perf_counter() - t) * 1e3
 
-    ms_partial, layer_ms = timed(lambda l: epp.epp_backward_aggregate(path_objs[l], grad_in[l], grad_out[l]),
-                                 args.steps, args.warmup)
+    run_partial = lambda l: epp.epp_backward_aggregate(path_objs[l], grad_in[l], grad_out[l])  # noqa: E731
+    ms_partial, layer_ms = timed(run_partial, args.steps, args.warmup)
     layer_spread = timed.spread
     for l in range(L):
         infos.append(path_objs[l].info())
@@ -242,15 +246,16 @@ def main():
         layers.append({
             "l": l, "F": F, "rows": i.n_rows, "sources": i.n_src, "nnz": i.nnz, "max_len": i.max_len,
             "group_size": i.group_size, "groups": i.n_groups, "split_rows": i.n_split_rows,
-            "ms": ms, "ms_median": layer_spread[l][0], "ms_min": layer_spread[l][1], "algorithmic_bytes": bmin, "roofline_GBs": bmin / ms / 1e6 if ms > 0 else None,
+            "ms": ms, "ms_median": layer_spread[l][0], "ms_min": layer_spread[l][1], "algorithmic_bytes": bmin,
+            "roofline_GBs": bmin / ms / 1e6 if ms > 0 else None,
             "roofline_frac": bmin / ms / 1e6 / HBM_PEAK_GBS if ms > 0 else None,
             "gather_GBs": bedge / ms / 1e6 if ms > 0 else None,
         })
     dom = max(layers, key=lambda d: d["ms"])
-    traffic, l2_hit = read_traffic(cfg.name).get(dom["l"], (None, None))
-    # the machine's own random-row gather rate (profiles/gather_rate_microbenchmark.md): 235 G lines/s from L2, 60 G lines/s beyond
+    traffic, l2_hit = read_traffic(cfg.name).get(dom["l"], (None, None)) if detail else (None, None)
     lines = dom["nnz"] * ((dom["F"] * 4 + 127) // 128)
-    model_ms = lines * ((1.0 - l2_hit) / 60e9 + l2_hit / 235e9) * 1e3 if l2_hit is not None else None
+    model_ms = (lines * ((1.0 - l2_hit) / GATHER_MISS_LINES_PER_S + l2_hit / GATHER_L2_LINES_PER_S) * 1e3
+                if l2_hit is not None else None)
     roofline = {
         "bound": "hbm", "kernel": f"k_aggregate (layer l={dom['l']}, F={dom['F']})",
         "achieved": dom["roofline_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -265,10 +270,6 @@ def main():
     }
 
     result = {
-        "metric": "backward_aggregation_ms_per_epoch", "value": ms_partial, "unit": "ms/epoch",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_partial,
-        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
-        "data": "synthetic",
         "config": {"workload": cfg.name, "n": g.n, "nnz": g.nnz, "undirected_edges": g.undirected_edges,
                    "L": L, "widths_l0_first": cfg.widths, "n_train": cfg.n_train,
                    "max_degree": int(np.diff(g.rowptr).max())},
@@ -313,7 +314,7 @@ def main():
 
     # combination stage of the backward loop on the active rows (reported beside the metric, never
     # part of it): W'(l) = Y(l)^T X'(l+1), Y'(l) = X'(l+1) W(l)^T with W(l) of F_l x F_{l+1}, F_L = F_{L-1}
-    if not args.no_combination and not args.layers:
+    if detail and not args.no_combination and not args.layers:
         widths = list(cfg.widths) + [cfg.widths[L - 1]]
         comb = []
         for l in order:
@@ -356,21 +357,30 @@ def main():
             del Y, W, G, Wg, ws
         result["combination_active_rows"] = {"dtype": "f32", "layers": comb}
 
-    # training runs other kernels between two aggregations: the same epoch with the caches flushed
-    # (1 GiB written) before every layer launch; the sum of the per-layer event times is reported
-    if args.cold:
+    if detail and not args.layers:
+        k_side = max(3, args.steps // 4)
+        # training runs other kernels between two aggregations: the same epoch with the caches flushed
+        # (1 GiB written) before every layer launch; the sum of the per-layer event times is reported
         scratch = torch.empty(1 << 28, dtype=torch.float32, device=dev)
-        _, cold_layer_ms = timed(lambda l: epp.epp_backward_aggregate(path_objs[l], grad_in[l], grad_out[l]),
-                                 max(3, args.steps // 4), 1, between=lambda: scratch.fill_(1.0))
+        _, cold_layer_ms = timed(run_partial, k_side, 1, between=lambda l: scratch.fill_(1.0))
         result["partially_active"]["cold_cache_ms_per_epoch"] = sum(cold_layer_ms.values())
         del scratch
+
+        # a caller that does not rely on "rows outside the path are never written" clears the whole
+        # n x F output before every layer launch; the clearing is inside the timed region here
+        def cleared(l):
+            grad_out[l].zero_()
+            run_partial(l)
+
+        ms_cleared, _ = timed(cleared, k_side, 1)
+        result["partially_active"]["ms_per_epoch_with_output_cleared_every_epoch"] = ms_cleared
 
     # launch-bound workloads: the same epoch captured once in a HIP graph and replayed
     if ms_partial < 1.0 and not args.layers:
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             for l in order:
-                epp.epp_backward_aggregate(path_objs[l], grad_in[l], grad_out[l])
+                run_partial(l)
         for _ in range(args.warmup):
             graph.replay()
         torch.cuda.synchronize()
@@ -379,10 +389,84 @@ def main():
             graph.replay()
         torch.cuda.synchronize()
         result["partially_active"]["hip_graph_ms_per_epoch"] = (time.perf_counter() - t) * 1e3 / args.steps
+        del graph
+    del grad_in, grad_out, paths, full, path_objs
+    torch.cuda.empty_cache()
+    return result, cfg
+
+
+def compact(r):
+    """What the headline line keeps of a side configuration."""
+    dom = max(r["partially_active"]["layers"], key=lambda d: d["ms"])
+    out = {
+        "workload": r["config"]["workload"], "n": r["config"]["n"], "nnz": r["config"]["nnz"], "L": r["config"]["L"],
+        "widths_l0_first": r["config"]["widths_l0_first"], "n_train": r["config"]["n_train"],
+        "partial_ms_per_epoch": r["partially_active"]["ms_per_epoch"],
+        "partial_layer_ms": {str(d["l"]): d["ms"] for d in r["partially_active"]["layers"]},
+        "all_active_ms_per_epoch": r.get("all_active", {}).get("ms_per_epoch"),
+        "if_else_ms_per_epoch": r.get("if_else", {}).get("ms_per_epoch"),
+        "speedup_partial_over_all_active": r.get("speedup_partial_over_all_active"),
+        "dominant_layer": {"l": dom["l"], "F": dom["F"], "ms": dom["ms"], "algorithmic_bytes": dom["algorithmic_bytes"],
+                           "roofline_frac": dom["roofline_frac"]},
+        "prepare_ms": r["prepare_ms"], "schedule_ms": r["schedule_ms"], "break_even_epochs": r.get("break_even_epochs"),
+        "path_bytes_over_csr_bytes": r["path_bytes_over_csr_bytes"],
+    }
+    if "hip_graph_ms_per_epoch" in r["partially_active"]:
+        out["hip_graph_ms_per_epoch"] = r["partially_active"]["hip_graph_ms_per_epoch"]
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=int(os.environ.get("EPP_BENCH_CONFIG", "5")),
+                    help="headline workload (metric, roofline, cpu_baseline); default 5, the largest")
+    ap.add_argument("--only", action="store_true", help="skip the compact report on the other configurations")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-all-active", action="store_true")
+    ap.add_argument("--no-combination", action="store_true", help="skip the combination-stage report")
+    ap.add_argument("--cpu-budget-s", type=float, default=15.0)
+    ap.add_argument("--layers", type=str, default="", help="comma list of layers to run (profiling); default all")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference point for the HBM byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (the path has no multi-GPU part); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2204_02662_amd as epp
+
+    epp.load_library()  # fails loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    head, cfg = run_config(args.config, args, detail=True)
+    ms_partial = head["partially_active"]["ms_per_epoch"]
+    result = {
+        "metric": "backward_aggregation_ms_per_epoch", "value": ms_partial, "unit": "ms/epoch",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_partial,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic", "kernel_sources": kernel_source_hash(),
+    }
+    result.update(head)
+
+    # the other benchmark configurations, timed in this same run (compact form)
+    if not args.only and not args.layers:
+        side = {}
+        for k in (1, 2, 3, 4, 5):
+            if k == args.config:
+                continue
+            r, c = run_config(k, args, detail=False)
+            side[f"cfg{k}"] = compact(r)
+            del r, c
+        result["configs"] = side
 
     if not args.no_cpu_baseline:
-        del grad_out
-        torch.cuda.empty_cache()
         result["cpu_baseline"] = cpu_baseline(cfg, args.cpu_budget_s)
     else:
         result["cpu_baseline"] = None
