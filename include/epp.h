@@ -11,6 +11,9 @@
  *   EPP_TUNE_GS           group size for every (path, F) that has none forced            [selector]
  *   EPP_TUNE_HOT_MB       budget of the hot source rows, 0 switches hot/cold marking off [96]
  *   EPP_TUNE_LOG2_SLICES  log2 of the XCD feature slices, 0..3                           [chosen per path]
+ *   EPP_TUNE_PART         source-partitioned layout: 0 never, 1 where it pays, 2 always  [1]
+ *   EPP_TUNE_PART_KB      L2 kilobytes per XCD given to the most referenced source rows  [3584]
+ *   EPP_TUNE_PART_MINLEN  shortest row that is cut into per-XCD sections                 [96]
  * None of them changes a result beyond the order of floating-point additions.
  *
  * Notation (paper, Table 1 / Sec. 3 / Sec. 4): V_t training set; N^k the k-neighbour set
@@ -88,6 +91,11 @@ typedef struct {
     int32_t group_size;     /* gs: entries per group (Sec. 2.2, Sec. 5)                     */
     int64_t n_groups;       /* ceil(nnz / gs)                                               */
     int64_t n_split_rows;   /* rows cut by a group boundary (summed from per-group pieces)  */
+    /* source-partitioned layout of that width (all 0 if it is not in use): the entries of long rows
+       whose source is among the most referenced ones are kept in one section per XCD */
+    int64_t part_rows;          /* rows cut into per-section shares                          */
+    int64_t part_hot_entries;   /* entries in the eight XCD sections                         */
+    int64_t part_partial_rows;  /* partial rows of F floats written and added up per launch  */
 } epp_path_info_t;
 
 /* Execution path preparing (Sec. 4): computes N^k for k = 0..L (Theorem 1) by backward

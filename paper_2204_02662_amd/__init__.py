@@ -91,7 +91,9 @@ class _PathInfo(ctypes.Structure):
     _fields_ = [("n", ctypes.c_int64), ("n_rows", ctypes.c_int64), ("nnz", ctypes.c_int64),
                 ("n_src", ctypes.c_int64), ("max_len", ctypes.c_int64), ("len_hist", ctypes.c_int64 * 32),
                 ("bytes", ctypes.c_int64), ("sched_F", ctypes.c_int32), ("group_size", ctypes.c_int32),
-                ("n_groups", ctypes.c_int64), ("n_split_rows", ctypes.c_int64)]
+                ("n_groups", ctypes.c_int64), ("n_split_rows", ctypes.c_int64),
+                ("part_rows", ctypes.c_int64), ("part_hot_entries", ctypes.c_int64),
+                ("part_partial_rows", ctypes.c_int64)]
 
 
 _lib = None
@@ -173,6 +175,9 @@ class PathInfo:
     group_size: int
     n_groups: int
     n_split_rows: int
+    part_rows: int = 0
+    part_hot_entries: int = 0
+    part_partial_rows: int = 0
 
 
 class Path_:
@@ -196,7 +201,8 @@ class Path_:
         raw = _PathInfo()
         _check(load_library().epp_path_info(self._h, ctypes.byref(raw)))
         return PathInfo(raw.n, raw.n_rows, raw.nnz, raw.n_src, raw.max_len, list(raw.len_hist), raw.bytes,
-                        raw.sched_F, raw.group_size, raw.n_groups, raw.n_split_rows)
+                        raw.sched_F, raw.group_size, raw.n_groups, raw.n_split_rows, raw.part_rows,
+                        raw.part_hot_entries, raw.part_partial_rows)
 
     def export(self):
         """(row_ids, rowptr, col, val) device tensors in canonical form."""

@@ -102,6 +102,16 @@ struct AggArgs {
     // if-else selective scheduling only: membership bitmaps of the layer's rows and sources
     const unsigned int* row_bits;
     const unsigned int* src_bits;
+    // source-partitioned layout only (part != 0): the entry array consists of 8 sections of entries
+    // whose sources belong to one partition of the most referenced sources each, followed by the
+    // section of all other entries; the groups of section x < 8 run on XCD x only.
+    int part;                  // 0: off; 1: on
+    int hot_rounds;            // rounds of 8 workgroups (one per XCD) that cover the longest hot section
+    int total_rounds;          // hot_rounds + rounds of the last section
+    int sec_g[10];             // first group of sections 0..8, then n_groups
+    int n;                     // a row target t >= n is row t - n of the partial rows of the cut rows
+                               // (float[slots][F]); INT_MAX without the partitioned layout
+    uintptr_t part_delta;      // address of that array minus address of row n of `out`
 };
 
 template <int VEC>
@@ -126,13 +136,18 @@ __global__ __launch_bounds__(kBlock) void k_combine_cut_rows(const int32_t* __re
                                                              const int32_t* __restrict__ row_ids, int gs, int F,
                                                              int log2Fp, const float* __restrict__ pieces,
                                                              const unsigned int* __restrict__ only_bits,
-                                                             float* __restrict__ out) {
+                                                             float* __restrict__ out, int n,
+                                                             float* __restrict__ vpart) {
     const int Fp = 1 << log2Fp;
     const int64_t k = ((int64_t)blockIdx.x * kBlock + threadIdx.x) >> log2Fp;
     if (k >= n_cut) return;
     const int32_t r = cut_rows[k];
-    const int32_t v = row_ids ? row_ids[r] : r;
+    int32_t v = row_ids ? row_ids[r] : r;
     if (only_bits && !((only_bits[v >> 5] >> (v & 31)) & 1u)) return;
+    if (vpart && v >= n) {  // partitioned layout: the row is one section's share of a vertex's list
+        out = vpart;
+        v -= n;
+    }
     const int64_t g0 = rowptr[r] / gs, g1 = ((int64_t)rowptr[r + 1] - 1) / gs;
     for (int f = threadIdx.x & (Fp - 1); f < F; f += Fp) {
         float sum = 0.0f;
@@ -146,6 +161,28 @@ __global__ __launch_bounds__(kBlock) void k_combine_cut_rows(const int32_t* __re
         }
         for (; g < g1; ++g) sum += pieces[(g * 2 + 1) * F + f];
         sum += pieces[(g1 * 2) * F + f];
+        out[(size_t)v * F + f] = sum;
+    }
+}
+
+// Partitioned layout: out[vertex(m), :] = sum of the partial rows of split row m (one per section in
+// which it has entries), in section order.  Fp lanes per row.
+__global__ __launch_bounds__(kBlock) void k_combine_sections(const int32_t* __restrict__ mvert,
+                                                             const int32_t* __restrict__ mptr, int64_t n_split, int F,
+                                                             int log2Fp, const float* __restrict__ vpart,
+                                                             float* __restrict__ out) {
+    const int Fp = 1 << log2Fp;
+    const int64_t m = ((int64_t)blockIdx.x * kBlock + threadIdx.x) >> log2Fp;
+    if (m >= n_split) return;
+    const int32_t v = mvert[m];
+    const int s0 = mptr[m], s1 = mptr[m + 1];
+    for (int f = threadIdx.x & (Fp - 1); f < F; f += Fp) {
+        float x[9];
+#pragma unroll
+        for (int i = 0; i < 9; ++i) x[i] = s0 + i < s1 ? vpart[(size_t)(s0 + i) * F + f] : 0.0f;
+        float sum = x[0];
+#pragma unroll
+        for (int i = 1; i < 9; ++i) sum += x[i];
         out[(size_t)v * F + f] = sum;
     }
 }
@@ -184,10 +221,26 @@ __global__ __launch_bounds__(kBlock, IFELSE ? ((COLD && VEC != 1) ? 4 : 5) : 4) 
     const int ns = 1 << a.log2ns;
     const int xcd = blockIdx.x & 7;
     const int slice = xcd & (ns - 1);
-    const int64_t qb = ((int64_t)(blockIdx.x >> 3) << (3 - a.log2ns)) + (xcd >> a.log2ns);
-    const int64_t g = qb * (kBlock >> LOG2T) + (threadIdx.x >> LOG2T);
+    int64_t g, g_end = a.n_groups;
+    if (!IFELSE && a.part) {  // (the if-else baseline walks the graph as it is given)
+        // Source-partitioned layout.  The first hot_rounds rounds of 8 workgroups are "hot":
+        // the workgroup on XCD x takes the next groups of section x, so that L2 x only ever
+        // holds the source rows of partition x.  The rounds after them share the last section.
+        // (Interleaving the two kinds of rounds, so that gathers served by L2 and gathers served
+        // from beyond it are in flight together, measured slower: 13.9 against 13.6 ms.)
+        const int i = blockIdx.x >> 3;
+        if (i < a.hot_rounds) {
+            g = a.sec_g[xcd] + (int64_t)i * (kBlock >> LOG2T) + (threadIdx.x >> LOG2T);
+            g_end = a.sec_g[xcd + 1];
+        } else {
+            g = a.sec_g[8] + ((int64_t)(i - a.hot_rounds) * 8 + xcd) * (kBlock >> LOG2T) + (threadIdx.x >> LOG2T);
+        }
+    } else {
+        const int64_t qb = ((int64_t)(blockIdx.x >> 3) << (3 - a.log2ns)) + (xcd >> a.log2ns);
+        g = qb * (kBlock >> LOG2T) + (threadIdx.x >> LOG2T);
+    }
     const unsigned gi = (unsigned)g;  // n_groups < 2^31
-    const bool has = g < a.n_groups;  // slots past the end idle through the loop (no early exit: LDS order)
+    const bool has = g < g_end;  // slots past the end idle through the loop (no early exit: LDS order)
     const int t = threadIdx.x & (T - 1);
     const int64_t j0 = has ? g * a.gs : 0;
     const int len = has ? (int)(std::min<int64_t>(j0 + a.gs, a.nnz) - j0) : 0;
@@ -309,7 +362,11 @@ __global__ __launch_bounds__(kBlock, IFELSE ? ((COLD && VEC != 1) ? 4 : 5) : 4) 
                             asm volatile("" : "+v"(gl));
                             if (fok) write_row<VEC>(a.pieces + (size_t)(2 * gl) * (size_t)a.F + f, acc);
                         } else if (wr) {
-                            write_row<VEC>(a.out + ((size_t)v * (size_t)a.F + f), acc);
+                            // (a target >= n is one section's share of a cut row: it goes to the array of
+                            // partial rows, addressed relative to `out` so that the store stays one instruction)
+                            uintptr_t base = reinterpret_cast<uintptr_t>(a.out);
+                            if constexpr (!IFELSE) base += v >= a.n ? a.part_delta : 0;
+                            write_row<VEC>(reinterpret_cast<float*>(base) + ((size_t)v * (size_t)a.F + f), acc);
                         }
 #pragma unroll
                         for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
@@ -369,7 +426,7 @@ void launch_one(hipStream_t s, const AggArgs& a) {
     const int64_t per_block = kBlock >> LOG2T;
     const int64_t blocks_per_slice = (a.n_groups + per_block - 1) / per_block;
     const int64_t xcds_per_slice = 8 >> a.log2ns;
-    const int64_t q = (blocks_per_slice + xcds_per_slice - 1) / xcds_per_slice;
+    const int64_t q = a.part ? a.total_rounds : (blocks_per_slice + xcds_per_slice - 1) / xcds_per_slice;
     const dim3 grid((unsigned)(q * 8)), block(kBlock);
     if (a.row_bits) {
         if (a.has_cold) hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, true, true>), grid, block, 0, s, a);
@@ -414,6 +471,7 @@ __host__ __device__ inline int count_bin(int k) {
 }
 inline int bin_floor(int bin) {
     if (bin < 8) return bin;  // bins 4..7 do not occur (k = 4..7 map to bins 8..11)
+    if (bin >= 124) return 0x7FFFFFFF;
     int e = bin >> 2, sub = bin & 3;
     return (4 + sub) << (e - 2);
 }
@@ -508,11 +566,12 @@ int epp_default_group_size(const epp_path* p, int F) {
     return 1 << e;
 }
 
-int epp_build_schedule(epp_path* p, int gs, hipStream_t s, Schedule** out) {
+int epp_build_schedule_over(const epp_path* p, const int32_t* rowptr, int64_t n_rows, int64_t nnz, int gs,
+                            hipStream_t s, Schedule** out) {
     Schedule* sc = new Schedule();
     struct Guard { Schedule* s; ~Guard() { delete s; } } guard{sc};
     sc->gs = gs;
-    const int64_t n_groups = (p->nnz + gs - 1) / gs;
+    const int64_t n_groups = (nnz + gs - 1) / gs;
     if (n_groups >= 0x7FFFFFFFll) { epp_set_error("too many groups"); return EPP_ERR_TOO_LARGE; }
     sc->n_groups = n_groups;
     const epp_alloc_t* al = epp_alloc_of(p);
@@ -523,7 +582,7 @@ int epp_build_schedule(epp_path* p, int gs, hipStream_t s, Schedule** out) {
         EPP_TRY(cnt.alloc(sizeof(unsigned int), al));
         EPP_HIP_TRY(hipMemsetAsync(cnt.p, 0, sizeof(unsigned int), s));
         hipLaunchKernelGGL(k_sched_groups, dim3((unsigned)((n_groups + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
-                           p->rowptr.as<int32_t>(), p->n_stream_rows, gs, n_groups, sc->group_row.as<int32_t>(),
+                           rowptr, n_rows, gs, n_groups, sc->group_row.as<int32_t>(),
                            sc->cut_rows.as<int32_t>(), cnt.as<unsigned int>());
         EPP_HIP_TRY(hipGetLastError());
         unsigned int h = 0;
@@ -532,21 +591,30 @@ int epp_build_schedule(epp_path* p, int gs, hipStream_t s, Schedule** out) {
         sc->n_split_rows = h;
     }
     guard.s = nullptr;
+    *out = sc;
+    return EPP_OK;
+}
+
+int epp_build_schedule(epp_path* p, int gs, hipStream_t s, Schedule** out) {
+    Schedule* sc = nullptr;
+    EPP_TRY(epp_build_schedule_over(p, p->rowptr.as<int32_t>(), p->n_stream_rows, p->nnz, gs, s, &sc));
     p->scheds.push_back(sc);
     *out = sc;
     return EPP_OK;
 }
 
 int epp_launch_aggregate(epp_path* p, Schedule* sc, int log2_slices, const float* in, float* out, int F, hipStream_t s,
-                         const unsigned int* row_bits, const unsigned int* src_bits) {
+                         const unsigned int* row_bits, const unsigned int* src_bits, const Partition* part) {
     int vec, log2T;
     const bool aligned16 = ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & 15) == 0;
     row_shape(F, aligned16, &vec, &log2T);
     // feature slices over the XCDs: each slice keeps whole 128-byte lines of a row
-    int log2ns = std::min(std::max(log2_slices, 0), 3);
+    int log2ns = part ? 0 : std::min(std::max(log2_slices, 0), 3);
     while (log2ns > 0 && ((log2T - log2ns) < 0 || ((vec * 4) << (log2T - log2ns)) < 128)) --log2ns;
     log2T -= log2ns;
-    const int32_t* row_ids = p->row_ids.p ? p->row_ids.as<int32_t>() : nullptr;
+    if (part) sc = part->sched;  // groups over the partitioned entry array
+    const int32_t* row_ids = part ? part->tgt.as<int32_t>() : (p->row_ids.p ? p->row_ids.as<int32_t>() : nullptr);
+    const int32_t* rowptr = part ? part->vptr.as<int32_t>() : p->rowptr.as<int32_t>();
     float* pieces = sc->pieces_for(F);
     if (sc->n_split_rows > 0 && !pieces) { epp_set_error("no partial-row buffer for F=%d", F); return EPP_ERR_INVALID_ARG; }
     if (p->n_empty_rows > 0 && !row_bits) {  // all-active graph: vertices without any entry become zero
@@ -557,10 +625,10 @@ int epp_launch_aggregate(epp_path* p, Schedule* sc, int log2_slices, const float
     }
     if (sc->n_groups > 0) {
         AggArgs a;
-        a.cv = reinterpret_cast<const int2v*>(p->cv.p);
+        a.cv = reinterpret_cast<const int2v*>(part ? part->cv2.p : p->cv.p);
         a.group_row = sc->group_row.as<int32_t>();
         a.row_ids = row_ids;
-        a.n_rows = p->n_stream_rows;
+        a.n_rows = part ? part->n_vrows : p->n_stream_rows;
         a.in = in;
         a.out = out;
         a.nnz = p->nnz;
@@ -572,6 +640,24 @@ int epp_launch_aggregate(epp_path* p, Schedule* sc, int log2_slices, const float
         a.pieces = pieces;
         a.row_bits = row_bits;
         a.src_bits = src_bits;
+        a.part = 0;
+        a.hot_rounds = a.total_rounds = 0;
+        for (int x = 0; x < 10; ++x) a.sec_g[x] = 0;
+        a.n = 0x7FFFFFFF;
+        a.part_delta = 0;
+        if (part) {
+            const int per_block = kBlock >> log2T;
+            int hot = 0;
+            for (int x = 0; x < 8; ++x) hot = std::max(hot, (part->sec_g[x + 1] - part->sec_g[x] + per_block - 1) / per_block);
+            const int64_t rest_blocks = ((int64_t)part->sec_g[9] - part->sec_g[8] + per_block - 1) / per_block;
+            a.part = 1;
+            a.hot_rounds = hot;
+            a.total_rounds = hot + (int)((rest_blocks + 7) / 8);
+            for (int x = 0; x < 10; ++x) a.sec_g[x] = part->sec_g[x];
+            a.n = (int)p->n;
+            a.part_delta = reinterpret_cast<uintptr_t>(part->vpart.p) - reinterpret_cast<uintptr_t>(out) -
+                           (uintptr_t)p->n * (uintptr_t)F * sizeof(float);
+        }
         // gathers in flight per lane: 8 x 16 bytes, or 16 narrower ones
         if (vec == 4) launch_vec<4, 8>(log2T, s, a);
         else if (vec == 2) launch_vec<2, 16>(log2T, s, a);
@@ -581,8 +667,15 @@ int epp_launch_aggregate(epp_path* p, Schedule* sc, int log2_slices, const float
         const int log2Fp = std::min(ceil_log2(F), 6);
         const int64_t total = sc->n_split_rows << log2Fp;
         hipLaunchKernelGGL(k_combine_cut_rows, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
-                           sc->cut_rows.as<int32_t>(), sc->n_split_rows, p->rowptr.as<int32_t>(), row_ids, sc->gs, F,
-                           log2Fp, pieces, row_bits, out);
+                           sc->cut_rows.as<int32_t>(), sc->n_split_rows, rowptr, row_ids, sc->gs, F,
+                           log2Fp, pieces, row_bits, out, (int)p->n, part ? part->vpart.as<float>() : (float*)nullptr);
+    }
+    if (part && part->n_split > 0) {
+        const int log2Fp = std::min(ceil_log2(F), 6);
+        const int64_t total = part->n_split << log2Fp;
+        hipLaunchKernelGGL(k_combine_sections, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
+                           part->mvert.as<int32_t>(), part->mptr.as<int32_t>(), part->n_split, F, log2Fp,
+                           part->vpart.as<float>(), out);
     }
     EPP_HIP_TRY(hipGetLastError());
     return EPP_OK;
@@ -596,83 +689,108 @@ int epp_launch_aggregate(epp_path* p, Schedule* sc, int log2_slices, const float
 // the often referenced ones.  The most referenced sources, as many as fit the budget, stay
 // "hot"; all entries of the others get the cold flag and are gathered with streaming loads.
 //
-// XCD feature slicing.  Two slices double the number of distinct rows an L2 can hold at the
-// price of reading the index stream twice and of touching twice as many rows per gather
-// instruction.  It pays when the hottest sources carry much of the traffic: it is switched on
-// when rows are at least 512 bytes and the sources that fit with slicing, but not without,
-// receive at least 6 % of all references (measured: R-MAT configuration, 8 % -> 16.5 to 15.3
-// ms; Chung-Lu configuration, 4 % -> 4.3 to 4.6 ms, left off).
-int epp_tune_locality(epp_path* p, int F, hipStream_t s, int* log2_slices) {
+// Source partition (epp_partition.hip).  The entries that reference the sources the eight L2s can
+// hold together are moved into one section per XCD; built where the counts say it pays.
+//
+// XCD feature slicing (only without the source partition).  Two slices double the number of
+// distinct rows an L2 can hold at the price of reading the index stream twice and of touching
+// twice as many rows per gather instruction.  It pays when the hottest sources carry much of the
+// traffic: it is switched on when rows are at least 512 bytes and the sources that fit with
+// slicing, but not without, receive at least 6 % of all references (measured: R-MAT
+// configuration, 8 % -> 16.5 to 15.3 ms; Chung-Lu configuration, 4 % -> 4.3 to 4.6 ms, left off).
+int epp_tune_locality(epp_path* p, int F, int gs, hipStream_t s, int* log2_slices, Partition** part) {
     const int64_t budget_mb = env_int("EPP_TUNE_HOT_MB", 96);
     const int64_t rows_budget = budget_mb * (1ll << 20) / ((int64_t)F * 4);
     const int forced_slices = env_int("EPP_TUNE_LOG2_SLICES", -1);
     *log2_slices = forced_slices >= 0 ? forced_slices : 0;
-    int thr = 0;
-    DevArena arena;
-    DevBuf cnt, hot;
+    *part = nullptr;
     // (measured useful for rows of 256 bytes and more; at F = 47 the extra branch costs 3 %)
-    if (budget_mb > 0 && p->nnz > 0 && p->n_src > rows_budget && (int64_t)F * 4 >= 256) {
-        // counts, histogram and hot bitmap share one allocation
-        const size_t hot_bytes = (size_t)((p->n + 63) / 64) * 8;
-        EPP_TRY(arena.reserve(DevArena::rounded((size_t)p->n * 4) + DevArena::rounded(kCountBins * sizeof(unsigned long long)) +
-                              DevArena::rounded(hot_bytes), epp_alloc_of(p)));
-        arena.take(&cnt, (size_t)p->n * 4);
-        EPP_HIP_TRY(hipMemsetAsync(cnt.p, 0, cnt.bytes, s));
-        DevBuf hist;
-        arena.take(&hist, kCountBins * sizeof(unsigned long long));
-        arena.take(&hot, hot_bytes);
-        EPP_HIP_TRY(hipMemsetAsync(hist.p, 0, hist.bytes, s));
-        // at most ~16 M sampled entries
-        const int64_t n_seg = (p->nnz + 63) / 64;
-        const int64_t stride = std::max<int64_t>(1, n_seg / (1 << 18));
-        const int64_t n_sampled_seg = (n_seg + stride - 1) / stride;
-        hipLaunchKernelGGL(k_count_sources, dim3((unsigned)((n_sampled_seg + (kBlock / 64) - 1) / (kBlock / 64))),
-                           dim3(kBlock), 0, s, reinterpret_cast<const int2v*>(p->cv.p), p->nnz, stride, cnt.as<int>());
-        hipLaunchKernelGGL(k_count_hist, dim3((unsigned)std::min<int64_t>((p->n + kBlock - 1) / kBlock, 2048)), dim3(kBlock), 0, s,
-                           cnt.as<int>(), p->n, hist.as<unsigned long long>());
-        EPP_HIP_TRY(hipGetLastError());
-        unsigned long long h[kCountBins];
-        EPP_HIP_TRY(hipMemcpyAsync(h, hist.p, sizeof(h), hipMemcpyDeviceToHost, s));
-        EPP_HIP_TRY(hipStreamSynchronize(s));
-        // keep whole bins, most referenced first, while they fit
+    if (p->nnz == 0 || (int64_t)F * 4 < 256) return EPP_OK;
+    const int64_t part_rows = forced_slices >= 0 ? 0 : epp_partition_hot_rows(F);  // a forced slicing is a measurement
+    const bool want_cold = budget_mb > 0 && p->n_src > rows_budget;
+    const bool want_part = env_int("EPP_TUNE_PART", 1) != 0 && part_rows > 0 && p->n_src > part_rows;
+    if (!want_cold && !want_part) return EPP_OK;
+
+    // sampled reference counts, their histogram, and two bitmaps, in one allocation
+    DevArena arena;
+    DevBuf cnt, hist, hot, part_hot;
+    const size_t hot_bytes = (size_t)((p->n + 63) / 64) * 8;
+    EPP_TRY(arena.reserve(DevArena::rounded((size_t)p->n * 4) + DevArena::rounded(kCountBins * sizeof(unsigned long long)) +
+                          2 * DevArena::rounded(hot_bytes), epp_alloc_of(p)));
+    arena.take(&cnt, (size_t)p->n * 4);
+    arena.take(&hist, kCountBins * sizeof(unsigned long long));
+    arena.take(&hot, hot_bytes);
+    arena.take(&part_hot, hot_bytes);
+    EPP_HIP_TRY(hipMemsetAsync(cnt.p, 0, cnt.bytes, s));
+    EPP_HIP_TRY(hipMemsetAsync(hist.p, 0, hist.bytes, s));
+    // at most ~16 M sampled entries
+    const int64_t n_seg = (p->nnz + 63) / 64;
+    const int64_t stride = std::max<int64_t>(1, n_seg / (1 << 18));
+    const int64_t n_sampled_seg = (n_seg + stride - 1) / stride;
+    hipLaunchKernelGGL(k_count_sources, dim3((unsigned)((n_sampled_seg + (kBlock / 64) - 1) / (kBlock / 64))),
+                       dim3(kBlock), 0, s, reinterpret_cast<const int2v*>(p->cv.p), p->nnz, stride, cnt.as<int>());
+    hipLaunchKernelGGL(k_count_hist, dim3((unsigned)std::min<int64_t>((p->n + kBlock - 1) / kBlock, 2048)), dim3(kBlock), 0, s,
+                       cnt.as<int>(), p->n, hist.as<unsigned long long>());
+    EPP_HIP_TRY(hipGetLastError());
+    unsigned long long h[kCountBins];
+    EPP_HIP_TRY(hipMemcpyAsync(h, hist.p, sizeof(h), hipMemcpyDeviceToHost, s));
+    EPP_HIP_TRY(hipStreamSynchronize(s));
+    // smallest reference count of the sources kept when whole bins, most referenced first, are
+    // taken while they fit `budget` rows (sources the sample never met are never kept)
+    auto threshold_for = [&](int64_t budget) {
         int64_t kept = 0;
         int c = kCountBins - 1;
         for (; c >= 1; --c) {
-            if (kept + (int64_t)h[c] > rows_budget) break;
+            if (kept + (int64_t)h[c] > budget) break;
             kept += (int64_t)h[c];
         }
-        // bins 1..c are cold
-        thr = c < 1 ? 1 : bin_floor(c + 1 == 4 ? 8 : c + 1);  // sources the sample never met are cold
+        return c < 1 ? 1 : bin_floor(c + 1 == 4 ? 8 : c + 1);  // bins 1..c are left out
+    };
 
-        if (forced_slices < 0 && (int64_t)F * 4 >= 512) {
-            // share of the references that goes to the sources ranked (rows one L2 holds) ..
-            // (twice that), estimated from the bins (a bin's sources count as its lower bound)
-            const int64_t l2_rows = (4ll << 20) / ((int64_t)F * 4);
-            double refs_between = 0.0;
-            int64_t rank = 0;
-            for (int b = kCountBins - 1; b >= 1; --b) {
-                const int64_t lo = std::max(rank, l2_rows), hi = std::min<int64_t>(rank + (int64_t)h[b], 2 * l2_rows);
-                if (hi > lo) refs_between += (double)(hi - lo) * (double)bin_floor(b);
-                rank += (int64_t)h[b];
+    if (want_cold) {
+        const int thr = threshold_for(rows_budget);
+        // One set of marks per path, shared by all its widths: it is the one chosen for the largest
+        // prepared width that marks at all (a smaller budget in rows; narrower widths then stream a
+        // few rows they could have kept).  The marks therefore depend on which widths have been
+        // prepared, never on the order of the calls.
+        if (F > p->cold_F) {
+            p->cold_F = F;
+            if (thr != p->cold_thr) {
+                hipLaunchKernelGGL(k_hot_bitmap, dim3((unsigned)((p->n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
+                                   cnt.as<int>(), p->n, thr, hot.as<unsigned long long>());
+                hipLaunchKernelGGL(k_mark_cold, dim3((unsigned)((p->nnz + 2 * kBlock - 1) / (2 * kBlock))), dim3(kBlock),
+                                   0, s, reinterpret_cast<int2v*>(p->cv.p), p->nnz, hot.as<unsigned int>());
+                EPP_HIP_TRY(hipGetLastError());
+                EPP_HIP_TRY(hipStreamSynchronize(s));
+                p->cold_thr = thr;
             }
-            if (refs_between >= 0.06 * (double)p->nnz / (double)stride) *log2_slices = 1;
         }
     }
-    // One set of marks per path, shared by all its widths: it is the one chosen for the largest
-    // prepared width that marks at all (a smaller budget in rows; narrower widths then stream a
-    // few rows they could have kept).  The marks therefore depend on which widths have been
-    // prepared, never on the order of the calls.
-    if (thr == 0 || F <= p->cold_F) return EPP_OK;
-    p->cold_F = F;
-    if (thr == p->cold_thr) return EPP_OK;
-    if (thr > 0) {
-        hipLaunchKernelGGL(k_hot_bitmap, dim3((unsigned)((p->n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
-                           cnt.as<int>(), p->n, thr, hot.as<unsigned long long>());
+
+    if (want_part) {
+        const int thr = threshold_for(part_rows);
+        if (thr < 0x7FFFFFFF) {
+            hipLaunchKernelGGL(k_hot_bitmap, dim3((unsigned)((p->n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
+                               cnt.as<int>(), p->n, thr, part_hot.as<unsigned long long>());
+            EPP_HIP_TRY(hipGetLastError());
+            EPP_TRY(epp_build_partition(p, F, gs, part_hot.as<unsigned int>(), s, part));
+        }
     }
-    hipLaunchKernelGGL(k_mark_cold, dim3((unsigned)((p->nnz + 2 * kBlock - 1) / (2 * kBlock))), dim3(kBlock), 0, s,
-                       reinterpret_cast<int2v*>(p->cv.p), p->nnz, thr > 0 ? hot.as<unsigned int>() : (const unsigned int*)nullptr);
-    EPP_HIP_TRY(hipGetLastError());
+
+    // (chosen whether or not the width has a partitioned layout: the if-else baseline never uses that layout)
+    if (forced_slices < 0 && (int64_t)F * 4 >= 512) {
+        // share of the references that goes to the sources ranked (rows one L2 holds) ..
+        // (twice that), estimated from the bins (a bin's sources count as its lower bound)
+        const int64_t l2_rows = (4ll << 20) / ((int64_t)F * 4);
+        double refs_between = 0.0;
+        int64_t rank = 0;
+        for (int b = kCountBins - 1; b >= 1; --b) {
+            const int64_t lo = std::max(rank, l2_rows), hi = std::min<int64_t>(rank + (int64_t)h[b], 2 * l2_rows);
+            if (hi > lo) refs_between += (double)(hi - lo) * (double)bin_floor(b);
+            rank += (int64_t)h[b];
+        }
+        if (refs_between >= 0.06 * (double)p->nnz / (double)stride) *log2_slices = 1;
+    }
     EPP_HIP_TRY(hipStreamSynchronize(s));
-    p->cold_thr = thr;
     return EPP_OK;
 }

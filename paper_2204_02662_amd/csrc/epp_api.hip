@@ -12,7 +12,7 @@ thread_local char g_err[512] = "";
 epp_path::WidthCfg* width_cfg(epp_path* p, int F) {
     for (auto& w : p->widths)
         if (w.F == F) return &w;
-    p->widths.push_back(epp_path::WidthCfg{F, 0, nullptr, 0});
+    p->widths.push_back(epp_path::WidthCfg{F, 0, nullptr, 0, nullptr});
     return &p->widths.back();
 }
 
@@ -31,7 +31,9 @@ int prepare_width(epp_path* p, int F, hipStream_t s, epp_path::WidthCfg** out) {
         Schedule* sc = find_schedule(p, gs);
         if (!sc) EPP_TRY(epp_build_schedule(p, gs, s, &sc));
         EPP_TRY(sc->ensure_pieces(F, epp_alloc_of(p)));
-        EPP_TRY(epp_tune_locality(p, F, s, &w->log2_slices));
+        delete w->part;
+        w->part = nullptr;
+        EPP_TRY(epp_tune_locality(p, F, gs, s, &w->log2_slices, &w->part));
         w->sched = sc;
     }
     p->last_F = F;
@@ -58,7 +60,9 @@ int aggregate(epp_path* p, const float* in, float* out, int F, hipStream_t s, co
         return EPP_ERR_INVALID_ARG;
     }
     p->last_F = F;
-    return epp_launch_aggregate(p, w->sched, w->log2_slices, in, out, F, s, row_bits, src_bits);
+    // (the if-else baseline walks the whole graph in its given order: no partitioned layout)
+    return epp_launch_aggregate(p, w->sched, w->log2_slices, in, out, F, s, row_bits, src_bits,
+                                row_bits ? nullptr : w->part);
 }
 
 }  // namespace
@@ -83,13 +87,21 @@ extern "C" int epp_path_info(const epp_path_t* p, epp_path_info_t* info) {
     for (int c = 0; c < EPP_NCLASS; ++c) info->len_hist[c] = p->len_hist[c];
     size_t bytes = p->row_ids.bytes + p->rowptr.bytes + p->cv.bytes + p->full_rowptr.bytes + p->empty_rows.bytes;
     for (const Schedule* s : p->scheds) bytes += s->bytes();
+    for (const auto& w : p->widths)
+        if (w.part) bytes += w.part->bytes();
     info->bytes = (int64_t)bytes;
     for (const auto& w : p->widths) {
         if (w.F == p->last_F && w.sched) {
+            const Schedule* used = w.part ? w.part->sched : w.sched;
             info->sched_F = w.F;
-            info->group_size = w.sched->gs;
-            info->n_groups = w.sched->n_groups;
-            info->n_split_rows = w.sched->n_split_rows;
+            info->group_size = used->gs;
+            info->n_groups = used->n_groups;
+            info->n_split_rows = used->n_split_rows;
+            if (w.part) {
+                info->part_rows = w.part->n_split;
+                info->part_hot_entries = w.part->hot_entries;
+                info->part_partial_rows = w.part->n_slots;
+            }
         }
     }
     return EPP_OK;
@@ -119,6 +131,8 @@ extern "C" int epp_path_set_group_size(epp_path_t* p, int F, int gs, epp_stream_
     w->forced_gs = gs > 0 ? gs : 0;
     if (w->sched) w->sched->drop_pieces(F);  // a table shared with other widths keeps theirs
     w->sched = nullptr;
+    delete w->part;
+    w->part = nullptr;
     // drop cached tables that no width refers to any more
     for (size_t i = 0; i < p->scheds.size();) {
         bool used = false;

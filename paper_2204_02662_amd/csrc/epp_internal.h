@@ -143,6 +143,31 @@ struct Schedule {
     }
 };
 
+// Source-partitioned layout of a path for one width ("reconstructed" execution path, Sec. 6's
+// pre-processing step, re-derived for a GPU of 8 XCDs with private L2s).  The entries of the long
+// rows whose source is among the most referenced ones are moved into 8 sections by partition of the
+// source; section x is processed by XCD x only, whose L2 then holds only the source rows of
+// partition x.  All other entries form the last section.  A row that has entries in several
+// sections becomes one virtual row per section; each writes a partial row to `vpart`, and a last
+// kernel adds a vertex's partial rows in section order.
+struct Partition {
+    DevBuf cv2;        // int2[nnz] entries, section after section, canonical order inside a section
+    DevBuf vptr;       // int32[n_vrows + 1] entry range of every virtual row
+    DevBuf tgt;        // int32[n_vrows] vertex id (< n) or n + slot in vpart
+    int64_t n_vrows = 0;
+    DevBuf mvert;      // int32[n_split] vertex of every row that is cut into sections
+    DevBuf mptr;       // int32[n_split + 1] its slots in vpart
+    int64_t n_split = 0, n_slots = 0;
+    DevBuf vpart;      // float[n_slots][F]
+    int sec_g[10] = {};    // first group of every section, then n_groups
+    int64_t hot_entries = 0;  // entries in the eight hot sections
+    Schedule* sched = nullptr;  // groups over (vptr, cv2)
+    ~Partition() { delete sched; }
+    size_t bytes() const {
+        return cv2.bytes + vptr.bytes + tgt.bytes + mvert.bytes + mptr.bytes + vpart.bytes + (sched ? sched->bytes() : 0);
+    }
+};
+
 struct epp_path {
     int64_t n = 0;       // vertices of the input graph
     int64_t n_rows = 0;  // R: rows of the path in canonical form (all-active graph: n)
@@ -167,10 +192,14 @@ struct epp_path {
     std::vector<Schedule*> scheds;
     // per-width choices
     // sched == NULL: the width has not been prepared (epp_path_prepare_width); slices: XCD feature slicing
-    struct WidthCfg { int F; int forced_gs; Schedule* sched; int log2_slices; };
+    // part: source-partitioned layout of this width, if it pays (owned by the path)
+    struct WidthCfg { int F; int forced_gs; Schedule* sched; int log2_slices; Partition* part; };
     std::vector<WidthCfg> widths;
     int last_F = 0;
-    ~epp_path() { for (Schedule* s : scheds) delete s; }
+    ~epp_path() {
+        for (Schedule* s : scheds) delete s;
+        for (auto& w : widths) delete w.part;
+    }
 };
 
 struct epp_paths {
@@ -207,8 +236,21 @@ int epp_static_scratch(float** ptr);
 // aggregate.hip
 int epp_build_schedule(epp_path* p, int gs, hipStream_t s, Schedule** out);
 int epp_launch_aggregate(epp_path* p, Schedule* sc, int log2_slices, const float* in, float* out, int F, hipStream_t s,
-                         const unsigned int* row_bits = nullptr, const unsigned int* src_bits = nullptr);
+                         const unsigned int* row_bits = nullptr, const unsigned int* src_bits = nullptr,
+                         const Partition* part = nullptr);
+// group table over any (row pointer, entry count); not registered with the path
+int epp_build_schedule_over(const epp_path* p, const int32_t* rowptr, int64_t n_rows, int64_t nnz, int gs, hipStream_t s,
+                            Schedule** out);
 int epp_default_group_size(const epp_path* p, int F);
-int epp_tune_locality(epp_path* p, int F, hipStream_t s, int* log2_slices);
+int epp_tune_locality(epp_path* p, int F, int gs, hipStream_t s, int* log2_slices, Partition** part);
+
+// partition.hip
+int epp_partition_hot_rows(int F);  // source rows of width F the eight L2s hold together
+// source-partitioned layout of `p` for width F and group size gs, or *out = NULL where it does not pay
+int epp_build_partition(epp_path* p, int F, int gs, const unsigned int* hot_bitmap, hipStream_t s, Partition** out);
+
+// prepare.hip: exclusive scan of n ints (*total, device, receives the sum); tmp: epp_scan_tmp_bytes(n)
+size_t epp_scan_tmp_bytes(int64_t n);
+void epp_scan_exclusive(const int* in, int* out, int64_t n, long long* total, int* tmp, hipStream_t s);
 inline const epp_alloc_t* epp_alloc_of(const epp_path* p) { return p->alloc.alloc ? &p->alloc : nullptr; }
 inline const epp_alloc_t* epp_alloc_of(const epp_paths* p) { return p->alloc.alloc ? &p->alloc : nullptr; }

@@ -508,6 +508,11 @@ int input_error(int bits, int64_t n) {
 
 }  // namespace
 
+size_t epp_scan_tmp_bytes(int64_t n) { return scan_tmp_bytes(n); }
+void epp_scan_exclusive(const int* in, int* out, int64_t n, long long* total, int* tmp, hipStream_t s) {
+    scan_counts(in, out, n, total, tmp, s);
+}
+
 void epp_path_set_stats(epp_path* p, const unsigned long long* host) {
     for (int c = 0; c < EPP_NCLASS; ++c) p->len_hist[c] = (int64_t)host[c];
     int mx;

@@ -316,6 +316,54 @@ def test_xcd_feature_slices_and_cold_marks_on_every_row(monkeypatch, F, slices, 
         assert_close(run_partial(p, Xp), want, f"slices 2^{slices} hot {hot_mb} MB F={F} l={l}, nan-poison")
 
 
+@pytest.mark.parametrize("F", [64, 67, 128, 130, 256])
+@pytest.mark.parametrize("min_len", ["4", "40"])
+def test_source_partitioned_layout_on_every_row(monkeypatch, F, min_len):
+    """The source-partitioned layout (entries of long rows that reference the most referenced
+    sources moved into one section per XCD, partial rows added up per vertex), forced on at a
+    small size with a hot set far smaller than the source set: every row against the oracle,
+    with the library's group size and with a small one that cuts many virtual rows, NaN poison
+    outside the source set, rows outside the path untouched, bit-identical repeats; the same for
+    the all-active graph, whose empty rows must still come out zero."""
+    g = graphgen.random_graph("rmat", 30_000, seed=271, raw_draws=400_000)
+    train = graphgen.training_set(g.n, 3000, 272)
+    sets_o, paths_o = oprep(g, train, 2)
+    monkeypatch.setenv("EPP_TUNE_PART", "2")
+    monkeypatch.setenv("EPP_TUNE_PART_KB", "64")
+    monkeypatch.setenv("EPP_TUNE_PART_MINLEN", min_len)
+    paths = gpu_prepare(g, train, 2)
+    for l, gs in ((0, 24), (0, 0), (1, 0)):
+        X = graphgen.normal_rows(g.n, F, sets_o[2 - l - 1], 273 + l)
+        want = oracle.path_aggregate(g.n, paths_o[l], X)
+        p = paths.path(l)
+        p.set_group_size(F, gs)
+        rows = sets_o[2 - l].astype(bool)
+        got = run_partial(p, X, poison=9.0)
+        i = p.info()
+        assert i.part_rows > 0 and i.part_hot_entries > 0 and i.part_partial_rows >= i.part_rows, i
+        if gs:
+            assert i.n_split_rows > 1000
+        assert np.all(got[~rows] == 9.0)
+        assert_close(got[rows], want[rows], f"partitioned F={F} l={l} gs={gs}")
+        again = run_partial(p, X, poison=float("nan"))
+        assert np.array_equal(got[rows], again[rows])
+        Xp = X.copy()
+        Xp[sets_o[2 - l - 1] == 0] = np.nan
+        assert_close(run_partial(p, Xp), want, f"partitioned F={F} l={l} gs={gs}, nan-poison")
+    assert_paths_bit_exact(paths, sets_o, paths_o, 2)  # the canonical form is not touched
+    full = gpu_prepare_full(g)
+    X = graphgen.normal_rows(g.n, F, None, 279)
+    got = run_full(full, X)
+    assert full.info().part_rows > 0
+    assert_close(got, oracle.full_aggregate(g.n, g.rowptr, g.col, g.val, X), f"partitioned all-active F={F}")
+    # the if-else baseline keeps walking the graph in its given order, whatever layout the width has
+    Xl = graphgen.normal_rows(g.n, F, sets_o[1], 273)
+    got = run_ifelse(full, paths, 0, Xl)
+    rows = sets_o[2].astype(bool)
+    assert np.all(got[~rows] == 123.0)
+    assert_close(got[rows], oracle.path_aggregate(g.n, paths_o[0], Xl)[rows], f"if-else beside the partition F={F}")
+
+
 def test_marks_of_a_path_do_not_depend_on_the_order_of_its_widths(monkeypatch):
     """One path used at two widths: the streamed-source marks are those of the wider width,
     whichever was prepared first, and results stay within tolerance either way."""
