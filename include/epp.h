@@ -137,8 +137,12 @@ int epp_active_set_export(const epp_paths_t* p, int k, int32_t* ids, int64_t* co
 
 /* Structure-aware group size (Sec. 5, re-derived for 64-lane wavefronts): the number gs of
  * consecutive entries of the path's edge array that form one group (the scheduling unit of
- * Sec. 2.2), as this library picks it for gradient width F from the path's size and
- * row-length histogram.  Pure function of (path, F); returns gs >= 1 or a negative error. */
+ * Sec. 2.2), as this library picks it for gradient width F.  As in Sec. 5 it is a linear regression
+ * on structural features of the sub-graph, fitted on a generated corpus: log2 gs is linear in
+ * log2(entries), log2(entries per row) and log2(F), rounded to a power of two in [8, 4096].  The
+ * row-length histogram that epp_path_info reports is informational: features taken from it (share
+ * of the entries in long rows, entry-weighted mean length, longest row) were fitted too and do not
+ * lower the leave-one-graph-out loss.  Pure function of (path, F); returns gs >= 1 or a negative error. */
 int epp_select_group_size(const epp_path_t* p, int F);
 
 /* The paper's linear-regression group size (Sec. 5, the regression equation and its four
