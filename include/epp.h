@@ -11,6 +11,8 @@
  *   EPP_TUNE_GS           group size for every (path, F) that has none forced            [selector]
  *   EPP_TUNE_HOT_MB       budget of the hot source rows, 0 switches hot/cold marking off [96]
  *   EPP_TUNE_LOG2_SLICES  log2 of the XCD feature slices, 0..3                           [chosen per path]
+ *   EPP_TUNE_SMALL_PREPARE  0: graphs of at most 65,536 vertices and 131,072 entries are prepared by the general
+ *                         construction instead of the single-launch one                     [1]
  *   EPP_TUNE_PART         source-partitioned layout: 0 never, 1 where it pays, 2 always  [1]
  *   EPP_TUNE_PART_KB      L2 kilobytes per XCD given to the most referenced source rows  [3584]
  *   EPP_TUNE_PART_MINLEN  shortest row that is cut into per-XCD sections                 [96]

@@ -209,6 +209,7 @@ struct epp_paths {
     std::vector<int64_t> set_size;  // |N^k|
     std::vector<epp_path*> path;    // index l; once the sets stop growing, deeper layers share one object
     DevBuf set0_ids;                // ascending ids of N^0 (the other sets are path rows)
+    DevBuf small_store;             // small graphs: the one allocation that all arrays above are views of
     epp_alloc_t alloc = {nullptr, nullptr, nullptr};
     ~epp_paths() {
         for (size_t i = 0; i < path.size(); ++i) {
@@ -227,6 +228,11 @@ int epp_path_finish(epp_path* p, hipStream_t s, void* stats_scratch = nullptr, u
 void epp_path_set_stats(epp_path* p, const unsigned long long* host);
 // ascending vertex ids of N^k (device, owned by `p`); allocates nothing, never waits
 int epp_active_ids(const epp_paths* p, int k, const int32_t** ids, int64_t* count);
+
+// prepare_small.hip: the whole construction in one launch, for graphs of at most 65,536 vertices and 131,072 entries
+bool epp_prepare_small_fits(const epp_csr_t* g, int64_t n_train, int L);
+int epp_prepare_small(const epp_csr_t* g, const int32_t* train_ids, int64_t n_train, int L, const epp_alloc_t* alloc,
+                      hipStream_t s, epp_paths_t** out);
 
 // combine.hip
 // device address of the static scratch array on the current GPU (symbol lookup once per device;

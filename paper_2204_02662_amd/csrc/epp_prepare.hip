@@ -14,6 +14,7 @@
 // alone yields the path's entries in canonical order.
 
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 
 #include "epp_internal.h"
@@ -562,6 +563,11 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
     {   // set-up of this GPU's static scratch array (used by epp_weight_gradient_static)
         float* unused = nullptr;
         EPP_TRY(epp_static_scratch(&unused));
+    }
+    // small graphs: one launch builds everything (EPP_TUNE_SMALL_PREPARE=0 forces the general construction)
+    if (epp_prepare_small_fits(g, n_train, L)) {
+        const char* e = std::getenv("EPP_TUNE_SMALL_PREPARE");
+        if (!(e && e[0] == '0')) return epp_prepare_small(g, train_ids, n_train, L, alloc, s, out);
     }
     const int64_t n = g->n, nnz = g->nnz;
     const int64_t n_words = (n + 63) / 64;

@@ -1,0 +1,352 @@
+// Execution path preparing (Sec. 4) for small graphs in ONE kernel launch.
+//
+// On a graph of a few thousand vertices the general construction (epp_prepare.hip) is all
+// overhead: about fifteen launches, a host wait and an allocation per level, against microseconds
+// of work.  Preparing on the fly (Sec. 6: the paths are built inside the first epoch) only pays if
+// the construction costs a few epochs' worth of savings, and on such graphs an epoch saves
+// microseconds.  Here one workgroup of 1024 threads builds every level with the frontier
+// bitmaps, the keep-mask of the entries and their prefix counts in LDS; the host makes one
+// allocation before (worst-case sizes: the whole handle is a megabyte or two), one launch, and one
+// wait after, for the sizes.  Same results as the general construction, bit for bit (tested).
+//
+// Limits: n, |V_t| <= 65,536 and nnz <= 131,072 (one LDS word per 64 vertices and thread, two per
+// 64 entries and thread), L <= 32.
+
+#include <algorithm>
+#include <cstring>
+
+#include "epp_internal.h"
+
+namespace {
+
+constexpr int kThreads = 1024;
+constexpr int kWaves = kThreads / 64;
+constexpr int kMaxItems = 65536;           // vertices
+constexpr int kWords = kMaxItems / 64;     // = kThreads: one bitmap word per thread
+constexpr int kMaxEntries = 2 * kMaxItems;
+constexpr int kEntryWords = kMaxEntries / 64;  // = 2 * kThreads: two keep-mask words per thread
+constexpr int kStatWords = EPP_NCLASS + 1; // histogram + longest row
+constexpr int kLevelWords = 3 + kStatWords; // kept entries, rows, "set did not change", statistics
+constexpr int kRowEnd = (int)0x80000000u;
+constexpr int kBatch = 8;                  // independent loads in flight per lane in the streaming loops
+
+__device__ __forceinline__ unsigned long long low_mask(int lane) { return (1ull << lane) - 1ull; }
+__device__ __forceinline__ int length_class(int len) { return len <= 1 ? 0 : 32 - __clz(len - 1); }
+
+// Exclusive scan of one value per thread over the workgroup; *total = sum.  (Two barriers.)
+__device__ __forceinline__ int block_scan(int x, int* wave_sum /* LDS, kWaves + 1 */, int* total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int incl = x;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int y = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += y;
+    }
+    __syncthreads();  // wave_sum may still be read from the scan before
+    if (lane == 63) wave_sum[wave] = incl;
+    __syncthreads();
+    int base = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const int s = wave_sum[w];
+        if (w < wave) base += s;
+        all += s;
+    }
+    *total = all;
+    return base + incl - x;
+}
+
+struct SmallArgs {
+    int n, nnz, n_train, L;
+    int cv_stride, ids_stride, ptr_stride, bm_stride;  // per-level strides of the output arrays, in elements
+    const int32_t* rowptr;
+    const int32_t* col;
+    const float* val;
+    const int32_t* train_ids;
+    unsigned long long* bitmaps;  // (L + 1) x n_words
+    int32_t* set0_ids;            // n
+    int2* cv;                     // L x nnz
+    int32_t* row_ids;             // L x n
+    int32_t* out_rowptr;          // L x (n + 1)
+    int* newptr;                  // n + 1 (scratch)
+    long long* result;            // [0] error bits, [1] |N^0|, then kLevelWords per level
+};
+
+__global__ __launch_bounds__(kThreads) void k_prepare_small(SmallArgs a) {
+    __shared__ unsigned long long bm_cur[kWords], bm_next[kWords], keep[kEntryWords];
+    __shared__ int wpre[kEntryWords], rpre[kWords];
+    __shared__ int wave_sum[kWaves + 1];
+    __shared__ int hist[EPP_NCLASS];
+    __shared__ int s_max, s_err, s_differs;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n_words = (a.n + 63) >> 6, n_seg = (a.nnz + 63) >> 6;
+
+    bm_cur[tid] = 0ull;
+    if (tid == 0) s_err = 0;
+    __syncthreads();
+    // N^0 = V_t (Property 1); the row pointer must rise from 0 to nnz
+    for (int i = tid; i < a.n_train; i += kThreads) {
+        const int v = a.train_ids[i];
+        if (v < 0 || v >= a.n) atomicOr(&s_err, 2);
+        else atomicOr(&bm_cur[v >> 6], 1ull << (v & 63));
+    }
+    for (int v = tid; v < a.n; v += kThreads) {
+        const int p0 = a.rowptr[v], p1 = a.rowptr[v + 1];
+        if (p0 < 0 || p1 < p0 || p1 > a.nnz || (v == 0 && p0 != 0) || (v == a.n - 1 && p1 != a.nnz)) atomicOr(&s_err, 1);
+    }
+    for (int e = tid; e < a.nnz; e += kThreads) {
+        const int c = a.col[e];
+        if (c < 0 || c >= a.n) atomicOr(&s_err, 4);
+    }
+    __syncthreads();
+    if (s_err) {  // uniform: nothing is indexed with unchecked values
+        if (tid == 0) a.result[0] = s_err;
+        return;
+    }
+    {   // ascending ids of N^0
+        int total;
+        const unsigned long long m = bm_cur[tid];
+        const int base = block_scan(__popcll(m), wave_sum, &total);
+        wpre[tid] = base;
+        __syncthreads();
+        for (int w = wave; w < n_words; w += kWaves) {
+            const unsigned long long mm = bm_cur[w];
+            if ((mm >> lane) & 1ull) a.set0_ids[wpre[w] + __popcll(mm & low_mask(lane))] = w * 64 + lane;
+        }
+        if (tid < n_words) a.bitmaps[tid] = m;
+        if (tid == 0) {
+            a.result[0] = 0;
+            a.result[1] = total;
+        }
+    }
+
+    for (int k = 0; k < a.L; ++k) {
+        int2* __restrict__ cv = a.cv + (size_t)k * a.cv_stride;
+        int32_t* __restrict__ row_ids = a.row_ids + (size_t)k * a.ids_stride;
+        int32_t* __restrict__ orp = a.out_rowptr + (size_t)k * a.ptr_stride;
+        __syncthreads();
+        bm_next[tid] = 0ull;
+        if (tid < EPP_NCLASS) hist[tid] = 0;
+        if (tid == 0) { s_max = 0; s_differs = 0; }
+        // keep-mask of the entries: is the column in N^k?  (kBatch words per step and wavefront: the
+        // column loads of a step are issued together, their latency is paid once)
+        for (int w0 = wave * kBatch; w0 < n_seg; w0 += kWaves * kBatch) {
+            int c[kBatch];
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) {
+                const int e = (w0 + i) * 64 + lane;
+                c[i] = e < a.nnz ? a.col[e] : -1;
+            }
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) {
+                const bool bit = c[i] >= 0 && ((bm_cur[c[i] >> 6] >> (c[i] & 63)) & 1ull);
+                const unsigned long long m = __ballot(bit);
+                if (lane == 0 && w0 + i < n_seg) keep[w0 + i] = m;
+            }
+        }
+        __syncthreads();
+        int kept;
+        {   // prefix counts of the keep-mask words: two consecutive words per thread
+            const int c0 = 2 * tid < n_seg ? __popcll(keep[2 * tid]) : 0;
+            const int c1 = 2 * tid + 1 < n_seg ? __popcll(keep[2 * tid + 1]) : 0;
+            const int wbase = block_scan(c0 + c1, wave_sum, &kept);
+            wpre[2 * tid] = wbase;
+            wpre[2 * tid + 1] = wbase + c0;
+        }
+        __syncthreads();
+        // stable compaction of (col, val)
+        for (int w0 = wave * kBatch; w0 < n_seg; w0 += kWaves * kBatch) {
+            int2 x[kBatch];
+            bool bit[kBatch];
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) {
+                const int w = w0 + i;
+                bit[i] = w < n_seg && ((keep[w] >> lane) & 1ull);
+                if (bit[i]) x[i] = make_int2(a.col[w * 64 + lane], __float_as_int(a.val[w * 64 + lane]));
+            }
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i)
+                if (bit[i]) cv[wpre[w0 + i] + __popcll(keep[w0 + i] & low_mask(lane))] = x[i];
+        }
+        // filtered row pointer of every vertex; a vertex with a non-empty filtered list is in N^{k+1}
+        for (int v0 = tid; v0 < a.n; v0 += kThreads * kBatch) {
+            int p0[kBatch], p1[kBatch];
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) {
+                const int v = v0 + i * kThreads;
+                p0[i] = v < a.n ? a.rowptr[v] : a.nnz;
+                p1[i] = v < a.n ? a.rowptr[v + 1] : a.nnz;
+            }
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) {
+                const int v = v0 + i * kThreads;
+                if (v >= a.n) continue;
+                const int ra = p0[i] >= a.nnz ? kept : wpre[p0[i] >> 6] + __popcll(keep[p0[i] >> 6] & low_mask(p0[i] & 63));
+                const int rb = p1[i] >= a.nnz ? kept : wpre[p1[i] >> 6] + __popcll(keep[p1[i] >> 6] & low_mask(p1[i] & 63));
+                a.newptr[v] = ra;
+                if (rb > ra) {
+                    atomicOr(&bm_next[v >> 6], 1ull << (v & 63));
+                    const int len = rb - ra;
+                    atomicAdd(&hist[length_class(len)], 1);
+                    atomicMax(&s_max, len);
+                }
+            }
+        }
+        __syncthreads();  // bm_next, newptr and the compacted entries are complete
+        int R;
+        const int rbase = block_scan(tid < n_words ? __popcll(bm_next[tid]) : 0, wave_sum, &R);
+        rpre[tid] = rbase;
+        if (tid < n_words && bm_next[tid] != bm_cur[tid]) s_differs = 1;
+        __syncthreads();
+        for (int w = wave; w < n_words; w += kWaves) {
+            const unsigned long long m = bm_next[w];
+            if ((m >> lane) & 1ull) {
+                const int v = w * 64 + lane;
+                const int r = rpre[w] + __popcll(m & low_mask(lane));
+                row_ids[r] = v;
+                orp[r] = a.newptr[v];
+                // last entry of the row: one before the next vertex's first kept entry
+                const int p1 = a.rowptr[v + 1];
+                const int rb = p1 >= a.nnz ? kept : wpre[p1 >> 6] + __popcll(keep[p1 >> 6] & low_mask(p1 & 63));
+                cv[rb - 1].x |= kRowEnd;
+            }
+        }
+        long long* res = a.result + 2 + (size_t)k * kLevelWords;
+        if (tid == 0) {
+            orp[R] = kept;
+            res[0] = kept;
+            res[1] = R;
+            res[2] = s_differs ? 0 : 1;
+            res[3 + EPP_NCLASS] = s_max;
+        }
+        if (tid < EPP_NCLASS) res[3 + tid] = hist[tid];
+        if (tid < n_words) a.bitmaps[(size_t)(k + 1) * a.bm_stride + tid] = bm_next[tid];
+        __syncthreads();
+        bm_cur[tid] = bm_next[tid];
+    }
+}
+
+// Pinned host words for the read-back, one buffer per host thread, kept for the thread's life.
+struct PinnedWords {
+    long long* p = nullptr;
+    size_t count = 0;
+    ~PinnedWords() { if (p) (void)hipHostFree(p); }
+    long long* get(size_t need) {
+        if (count < need) {
+            if (p) (void)hipHostFree(p);
+            p = nullptr;
+            count = 0;
+            if (hipHostMalloc((void**)&p, need * sizeof(long long), hipHostMallocDefault) != hipSuccess) {
+                (void)hipGetLastError();
+                p = nullptr;
+                return nullptr;
+            }
+            count = need;
+        }
+        return p;
+    }
+};
+thread_local PinnedWords g_pinned;
+
+}  // namespace
+
+bool epp_prepare_small_fits(const epp_csr_t* g, int64_t n_train, int L) {
+    return g->n <= kMaxItems && g->nnz <= kMaxEntries && n_train <= kMaxItems && L <= 32 && g->n > 0;
+}
+
+int epp_prepare_small(const epp_csr_t* g, const int32_t* train_ids, int64_t n_train, int L, const epp_alloc_t* alloc,
+                      hipStream_t s, epp_paths_t** out) {
+    const int64_t n = g->n, nnz = g->nnz, n_words = (n + 63) / 64;
+    epp_paths* P = new epp_paths();
+    struct Guard { epp_paths* p; ~Guard() { delete p; } } guard{P};
+    P->L = L;
+    P->n = n;
+    if (alloc && alloc->alloc && alloc->free) P->alloc = *alloc;
+    const epp_alloc_t* al = epp_alloc_of(P);
+    P->bitmaps.resize(L + 1);
+    P->set_size.assign(L + 1, 0);
+    P->path.assign(L, nullptr);
+
+    // one allocation for the whole handle (worst-case sizes), carved into 256-byte aligned pieces
+    const size_t result_words = 2 + (size_t)L * kLevelWords;
+    const size_t bm_bytes = (size_t)n_words * 8, cv_bytes = (size_t)std::max<int64_t>(nnz, 1) * 8,
+                 ids_bytes = (size_t)n * 4, ptr_bytes = (size_t)(n + 1) * 4;
+    DevArena arena;
+    EPP_TRY(arena.reserve((size_t)(L + 1) * DevArena::rounded(bm_bytes) + DevArena::rounded(ids_bytes) +
+                          (size_t)L * (DevArena::rounded(cv_bytes) + DevArena::rounded(ids_bytes) + DevArena::rounded(ptr_bytes)) +
+                          DevArena::rounded(ptr_bytes) + DevArena::rounded(result_words * 8), al));
+    // (every level's arrays start 256-byte aligned: the strides are the rounded sizes)
+    DevBuf bm_all, set0, cv_all, ids_all, ptr_all, newptr, result;
+    arena.take(&bm_all, (size_t)(L + 1) * DevArena::rounded(bm_bytes));
+    arena.take(&set0, ids_bytes);
+    arena.take(&cv_all, (size_t)L * DevArena::rounded(cv_bytes));
+    arena.take(&ids_all, (size_t)L * DevArena::rounded(ids_bytes));
+    arena.take(&ptr_all, (size_t)L * DevArena::rounded(ptr_bytes));
+    arena.take(&newptr, ptr_bytes);
+    arena.take(&result, result_words * 8);
+    long long* host = g_pinned.get(result_words);
+    if (!host) { epp_set_error("pinned host allocation failed"); return EPP_ERR_ALLOC; }
+
+    SmallArgs a;
+    a.n = (int)n;
+    a.nnz = (int)nnz;
+    a.n_train = (int)n_train;
+    a.L = L;
+    a.cv_stride = (int)(DevArena::rounded(cv_bytes) / 8);
+    a.ids_stride = (int)(DevArena::rounded(ids_bytes) / 4);
+    a.ptr_stride = (int)(DevArena::rounded(ptr_bytes) / 4);
+    a.bm_stride = (int)(DevArena::rounded(bm_bytes) / 8);
+    a.rowptr = g->rowptr;
+    a.col = g->col;
+    a.val = g->val;
+    a.train_ids = train_ids;
+    a.bitmaps = bm_all.as<unsigned long long>();
+    a.set0_ids = set0.as<int32_t>();
+    a.cv = cv_all.as<int2>();
+    a.row_ids = ids_all.as<int32_t>();
+    a.out_rowptr = ptr_all.as<int32_t>();
+    a.newptr = newptr.as<int>();
+    a.result = result.as<long long>();
+    hipLaunchKernelGGL(k_prepare_small, dim3(1), dim3(kThreads), 0, s, a);
+    EPP_HIP_TRY(hipGetLastError());
+    EPP_HIP_TRY(hipMemcpyAsync(host, result.p, result_words * 8, hipMemcpyDeviceToHost, s));
+    EPP_HIP_TRY(hipStreamSynchronize(s));
+    if (host[0] != 0) {
+        if (host[0] & 2) { epp_set_error("training id outside [0, %lld)", (long long)n); return EPP_ERR_OUT_OF_RANGE_ID; }
+        if (host[0] & 4) { epp_set_error("a column id lies outside [0, %lld)", (long long)n); return EPP_ERR_OUT_OF_RANGE_ID; }
+        epp_set_error("the row pointer does not rise from 0 to nnz");
+        return EPP_ERR_INVALID_ARG;
+    }
+    for (int k = 0; k <= L; ++k) P->bitmaps[k].view(bm_all.as<unsigned long long>() + (size_t)k * a.bm_stride, bm_bytes);
+    P->set_size[0] = host[1];
+    P->set0_ids.view(set0.p, (size_t)host[1] * 4);
+    for (int k = 0; k < L; ++k) {
+        const long long* res = host + 2 + (size_t)k * kLevelWords;
+        const int l = L - 1 - k;
+        epp_path* p = new epp_path();
+        P->path[l] = p;
+        p->n = n;
+        p->alloc = P->alloc;
+        p->n_src = P->set_size[k];
+        p->nnz = res[0];
+        p->n_rows = p->n_stream_rows = res[1];
+        P->set_size[k + 1] = res[1];
+        p->cv.view(cv_all.as<int2>() + (size_t)k * a.cv_stride, (size_t)res[0] * 8);
+        p->row_ids.view(ids_all.as<int32_t>() + (size_t)k * a.ids_stride, (size_t)res[1] * 4);
+        p->rowptr.view(ptr_all.as<int32_t>() + (size_t)k * a.ptr_stride, (size_t)(res[1] + 1) * 4);
+        for (int c = 0; c < EPP_NCLASS; ++c) p->len_hist[c] = res[3 + c];
+        p->max_len = res[3 + EPP_NCLASS];
+        // fixed point: N^{k+1} == N^k makes every deeper layer this very path
+        if (res[2] && k + 1 < L) {
+            for (int j = k + 1; j < L; ++j) {
+                P->set_size[j + 1] = P->set_size[k + 1];
+                P->path[L - 1 - j] = p;
+            }
+            break;
+        }
+    }
+    P->small_store = std::move(arena.store);
+    guard.p = nullptr;
+    *out = P;
+    return EPP_OK;
+}

@@ -20,6 +20,14 @@ if torch.cuda.is_available():
                        run_ifelse, dev)
 
 
+@pytest.fixture(params=["one-launch", "general"])
+def construction(request, monkeypatch):
+    """Small graphs are prepared by a single-launch construction; with EPP_TUNE_SMALL_PREPARE=0 they
+    go through the general one.  Tests on small graphs that take this fixture cover both."""
+    monkeypatch.setenv("EPP_TUNE_SMALL_PREPARE", "1" if request.param == "one-launch" else "0")
+    return request.param
+
+
 def oprep(g, train, L):
     return oracle.prepare(g.n, g.rowptr, g.col, g.val, np.asarray(train, np.int32), L)
 
@@ -62,7 +70,7 @@ def check_layers(g, train, L, widths, seed, gs_list=(0,)):
     return paths
 
 
-def test_worked_example_on_gpu():
+def test_worked_example_on_gpu(construction):
     edges = [(0, 1), (1, 2), (1, 3), (1, 4), (2, 3), (3, 4)]
     g = graphgen.csr_from_edges(5, edges, self_loops=False, normalise=False)
     paths = check_layers(g, [2, 4], 2, [3, 5], 1)
@@ -73,7 +81,7 @@ def test_worked_example_on_gpu():
 
 
 @pytest.mark.parametrize("seed", range(4))
-def test_small_random_graphs(seed):
+def test_small_random_graphs(seed, construction):
     rng = np.random.default_rng(seed)
     n = int(rng.integers(50, 400))
     sym = bool(seed & 1)
@@ -145,7 +153,7 @@ def test_group_size_invariance_and_group_counts():
     assert p.info().group_size == p.select_group_size(F) >= 1
 
 
-def test_special_cases_on_gpu():
+def test_special_cases_on_gpu(construction):
     rng = np.random.default_rng(3)
     n = 300
     edges = [(int(u), int(v)) for u, v in rng.integers(0, n, (900, 2)) if u != v]
@@ -167,7 +175,7 @@ def test_special_cases_on_gpu():
     assert np.all(run_full(gpu_prepare_full(g0), graphgen.normal_rows(10, 4, None, 1)) == 0.0)
 
 
-def test_error_paths():
+def test_error_paths(construction):
     g = graphgen.csr_from_edges(10, [(0, 1), (1, 2)], self_loops=True)
     with pytest.raises(epp.EppError) as e:
         gpu_prepare(g, [10], 2)
@@ -262,7 +270,7 @@ def test_forward_aggregation_and_its_adjoint():
 
 
 @pytest.mark.parametrize("k", [1, 2])
-def test_small_configs_every_entry(k):
+def test_small_configs_every_entry(k, construction):
     cfg = graphgen.make_config(k)
     check_layers(cfg.graph, cfg.train_ids, cfg.L, cfg.widths, cfg.seed(10))
 
@@ -443,7 +451,7 @@ def test_caller_allocator_owns_every_byte_and_aggregation_never_allocates():
         del free0
 
 
-def test_deep_model_shares_the_saturated_path():
+def test_deep_model_shares_the_saturated_path(construction):
     """Once N^{k+1} == N^k every deeper layer has the same execution path: it is built once."""
     n = 40
     g = graphgen.csr_from_edges(n, [(i, (i + 1) % n) for i in range(n)], self_loops=True)
@@ -499,7 +507,7 @@ def test_epoch_captured_in_a_hip_graph_replays_correctly():
             assert torch.equal(ys[l][~rows[l]], keep[l])  # rows outside the path untouched
 
 
-def test_randomised_shapes():
+def test_randomised_shapes(construction):
     """Many small random problems: graph shape, direction, self-loops, depth, width, group size."""
     rng = np.random.default_rng(2024)
     for case in range(60):
