@@ -200,8 +200,13 @@ __global__ __launch_bounds__(kBlock) void k_combine_sections(const int32_t* __re
 // The membership tests of the if-else variant cost a few registers, enough to lose a
 // wavefront per SIMD; its register budget is capped to the occupancy of the plain kernel
 // (five wavefronts per SIMD, four where the hot/cold branch of 8- and 16-byte lanes needs more).
-template <int VEC, int LOG2T, int U_, bool IFELSE, bool COLD>
+//
+// PART: the source-partitioned layout (block-to-group mapping by XCD, targets in the array of
+// partial rows).  A variant of its own, so that the plain kernels keep their register budget (the
+// few registers the extra addressing needs cost the 4-byte-lane kernel a wavefront per SIMD).
+template <int VEC, int LOG2T, int U_, bool IFELSE, bool COLD, bool PART>
 __global__ __launch_bounds__(kBlock, IFELSE ? ((COLD && VEC != 1) ? 4 : 5) : 4) void k_aggregate(AggArgs a) {
+    static_assert(!(IFELSE && PART), "the if-else baseline walks the graph as it is given");
     constexpr int T = 1 << LOG2T;
     constexpr int S = 4 * T;              // pairs staged per slot
     constexpr int U = U_ < S ? U_ : S;    // S is a multiple of U
@@ -222,7 +227,7 @@ __global__ __launch_bounds__(kBlock, IFELSE ? ((COLD && VEC != 1) ? 4 : 5) : 4) 
     const int xcd = blockIdx.x & 7;
     const int slice = xcd & (ns - 1);
     int64_t g, g_end = a.n_groups;
-    if (!IFELSE && a.part) {  // (the if-else baseline walks the graph as it is given)
+    if constexpr (PART) {
         // Source-partitioned layout.  The first hot_rounds rounds of 8 workgroups are "hot":
         // the workgroup on XCD x takes the next groups of section x, so that L2 x only ever
         // holds the source rows of partition x.  The rounds after them share the last section.
@@ -365,7 +370,7 @@ __global__ __launch_bounds__(kBlock, IFELSE ? ((COLD && VEC != 1) ? 4 : 5) : 4) 
                             // (a target >= n is one section's share of a cut row: it goes to the array of
                             // partial rows, addressed relative to `out` so that the store stays one instruction)
                             uintptr_t base = reinterpret_cast<uintptr_t>(a.out);
-                            if constexpr (!IFELSE) base += v >= a.n ? a.part_delta : 0;
+                            if constexpr (PART) base += v >= a.n ? a.part_delta : 0;
                             write_row<VEC>(reinterpret_cast<float*>(base) + ((size_t)v * (size_t)a.F + f), acc);
                         }
 #pragma unroll
@@ -429,11 +434,14 @@ void launch_one(hipStream_t s, const AggArgs& a) {
     const int64_t q = a.part ? a.total_rounds : (blocks_per_slice + xcds_per_slice - 1) / xcds_per_slice;
     const dim3 grid((unsigned)(q * 8)), block(kBlock);
     if (a.row_bits) {
-        if (a.has_cold) hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, true, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, true, false>), grid, block, 0, s, a);
+        if (a.has_cold) hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, true, true, false>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, true, false, false>), grid, block, 0, s, a);
+    } else if (a.part) {
+        if (a.has_cold) hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, false, true, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, false, false, true>), grid, block, 0, s, a);
     } else {
-        if (a.has_cold) hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, false, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, false, false>), grid, block, 0, s, a);
+        if (a.has_cold) hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, false, true, false>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, false, false, false>), grid, block, 0, s, a);
     }
 }
 
@@ -655,7 +663,7 @@ int epp_launch_aggregate(epp_path* p, Schedule* sc, int log2_slices, const float
             a.total_rounds = hot + (int)((rest_blocks + 7) / 8);
             for (int x = 0; x < 10; ++x) a.sec_g[x] = part->sec_g[x];
             a.n = (int)p->n;
-            a.part_delta = reinterpret_cast<uintptr_t>(part->vpart.p) - reinterpret_cast<uintptr_t>(out) -
+            a.part_delta = reinterpret_cast<uintptr_t>(part->vpart) - reinterpret_cast<uintptr_t>(out) -
                            (uintptr_t)p->n * (uintptr_t)F * sizeof(float);
         }
         // gathers in flight per lane: 8 x 16 bytes, or 16 narrower ones
@@ -668,14 +676,14 @@ int epp_launch_aggregate(epp_path* p, Schedule* sc, int log2_slices, const float
         const int64_t total = sc->n_split_rows << log2Fp;
         hipLaunchKernelGGL(k_combine_cut_rows, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
                            sc->cut_rows.as<int32_t>(), sc->n_split_rows, rowptr, row_ids, sc->gs, F,
-                           log2Fp, pieces, row_bits, out, (int)p->n, part ? part->vpart.as<float>() : (float*)nullptr);
+                           log2Fp, pieces, row_bits, out, (int)p->n, part ? part->vpart : (float*)nullptr);
     }
     if (part && part->n_split > 0) {
         const int log2Fp = std::min(ceil_log2(F), 6);
         const int64_t total = part->n_split << log2Fp;
         hipLaunchKernelGGL(k_combine_sections, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
                            part->mvert.as<int32_t>(), part->mptr.as<int32_t>(), part->n_split, F, log2Fp,
-                           part->vpart.as<float>(), out);
+                           part->vpart, out);
     }
     EPP_HIP_TRY(hipGetLastError());
     return EPP_OK;
@@ -705,10 +713,15 @@ int epp_tune_locality(epp_path* p, int F, int gs, hipStream_t s, int* log2_slice
     *log2_slices = forced_slices >= 0 ? forced_slices : 0;
     *part = nullptr;
     // (measured useful for rows of 256 bytes and more; at F = 47 the extra branch costs 3 %)
-    if (p->nnz == 0 || (int64_t)F * 4 < 256) return EPP_OK;
+    const int part_mode = env_int("EPP_TUNE_PART", 1);
+    if (p->nnz == 0 || ((int64_t)F * 4 < 256 && part_mode != 2)) return EPP_OK;
     const int64_t part_rows = forced_slices >= 0 ? 0 : epp_partition_hot_rows(F);  // a forced slicing is a measurement
-    const bool want_cold = budget_mb > 0 && p->n_src > rows_budget;
-    const bool want_part = env_int("EPP_TUNE_PART", 1) != 0 && part_rows > 0 && p->n_src > part_rows;
+    const bool want_cold = budget_mb > 0 && p->n_src > rows_budget && (int64_t)F * 4 >= 256;
+    // (in the automatic mode only where the source rows do not fit the eight L2s together; forced,
+    // for tests and measurements, at any width and size: on a graph whose narrow source rows all fit,
+    // it lifts the L2 hit rate from 62-76 % to 93 % and the time stays the same, because such
+    // launches are bound by the rate at which a CU's address unit and L1 take gather requests)
+    const bool want_part = part_rows > 0 && (part_mode == 2 || (part_mode == 1 && p->n_src > part_rows));
     if (!want_cold && !want_part) return EPP_OK;
 
     // sampled reference counts, their histogram, and two bitmaps, in one allocation

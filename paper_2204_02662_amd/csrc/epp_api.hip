@@ -30,10 +30,12 @@ int prepare_width(epp_path* p, int F, hipStream_t s, epp_path::WidthCfg** out) {
         const int gs = w->forced_gs > 0 ? w->forced_gs : epp_default_group_size(p, F);
         Schedule* sc = find_schedule(p, gs);
         if (!sc) EPP_TRY(epp_build_schedule(p, gs, s, &sc));
-        EPP_TRY(sc->ensure_pieces(F, epp_alloc_of(p)));
         delete w->part;
         w->part = nullptr;
         EPP_TRY(epp_tune_locality(p, F, gs, s, &w->log2_slices, &w->part));
+        // partial rows of the plain group table: not needed where every launch uses the partitioned
+        // layout (the all-active handle also serves the if-else baseline, which never does)
+        if (!w->part || p->all_rows) EPP_TRY(sc->ensure_pieces(F, epp_alloc_of(p)));
         w->sched = sc;
     }
     p->last_F = F;
@@ -89,6 +91,7 @@ extern "C" int epp_path_info(const epp_path_t* p, epp_path_info_t* info) {
     for (const Schedule* s : p->scheds) bytes += s->bytes();
     for (const auto& w : p->widths)
         if (w.part) bytes += w.part->bytes();
+    if (p->pool->accounted_by == p) bytes += p->pool->bytes();  // shared by the handle's paths: reported once
     info->bytes = (int64_t)bytes;
     for (const auto& w : p->widths) {
         if (w.F == p->last_F && w.sched) {

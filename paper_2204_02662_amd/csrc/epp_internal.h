@@ -143,6 +143,36 @@ struct Schedule {
     }
 };
 
+// Scratch memory of a launch that the paths of one handle share: a handle is used by one call at
+// a time, so two of its paths never need their scratch at once.  Buffers only ever get added (a
+// captured HIP graph may hold the address of an older one); a request is served by the smallest
+// buffer that is large enough, else by a new one, sized an eighth above the request at most so
+// that paths of nearly equal size end up on one buffer.
+struct ScratchPool {
+    std::vector<DevBuf*> bufs;
+    const void* accounted_by = nullptr;  // the path whose footprint report includes the pool
+    ~ScratchPool() { for (DevBuf* b : bufs) delete b; }
+    int get(size_t bytes, const epp_alloc_t* al, void** out) {
+        DevBuf* best = nullptr;
+        for (DevBuf* b : bufs)
+            if (b->bytes >= bytes && (!best || b->bytes < best->bytes)) best = b;
+        if (!best) {
+            size_t step = 256;
+            while (step * 16 <= bytes) step *= 2;  // an eighth of the leading power of two
+            best = new DevBuf();
+            if (best->alloc((bytes + step - 1) / step * step, al) != EPP_OK) { delete best; return EPP_ERR_ALLOC; }
+            bufs.push_back(best);
+        }
+        *out = best->p;
+        return EPP_OK;
+    }
+    size_t bytes() const {
+        size_t b = 0;
+        for (const DevBuf* x : bufs) b += x->bytes;
+        return b;
+    }
+};
+
 // Source-partitioned layout of a path for one width ("reconstructed" execution path, Sec. 6's
 // pre-processing step, re-derived for a GPU of 8 XCDs with private L2s).  The entries of the long
 // rows whose source is among the most referenced ones are moved into 8 sections by partition of the
@@ -158,13 +188,13 @@ struct Partition {
     DevBuf mvert;      // int32[n_split] vertex of every row that is cut into sections
     DevBuf mptr;       // int32[n_split + 1] its slots in vpart
     int64_t n_split = 0, n_slots = 0;
-    DevBuf vpart;      // float[n_slots][F]
+    float* vpart = nullptr;  // float[n_slots][F], in the handle's scratch pool
     int sec_g[10] = {};    // first group of every section, then n_groups
     int64_t hot_entries = 0;  // entries in the eight hot sections
     Schedule* sched = nullptr;  // groups over (vptr, cv2)
     ~Partition() { delete sched; }
     size_t bytes() const {
-        return cv2.bytes + vptr.bytes + tgt.bytes + mvert.bytes + mptr.bytes + vpart.bytes + (sched ? sched->bytes() : 0);
+        return cv2.bytes + vptr.bytes + tgt.bytes + mvert.bytes + mptr.bytes + (sched ? sched->bytes() : 0);
     }
 };
 
@@ -185,6 +215,8 @@ struct epp_path {
     int cold_thr = 0;            // entries whose source is referenced fewer times than this carry the cold flag
     int cold_F = 0;              // width the cold flags were chosen for (the largest prepared width that marks)
     epp_alloc_t alloc = {nullptr, nullptr, nullptr};  // the caller's allocator (alloc == NULL: hipMalloc)
+    ScratchPool own_pool;        // launch scratch of a path that belongs to no epp_paths handle
+    ScratchPool* pool = &own_pool;  // the handle's pool for the paths of an epp_paths handle
     // all-active graph only
     DevBuf full_rowptr;          // int32[n + 1] as given (for export)
     int64_t n_empty_rows = 0;
@@ -210,6 +242,7 @@ struct epp_paths {
     std::vector<epp_path*> path;    // index l; once the sets stop growing, deeper layers share one object
     DevBuf set0_ids;                // ascending ids of N^0 (the other sets are path rows)
     DevBuf small_store;             // small graphs: the one allocation that all arrays above are views of
+    ScratchPool pool;               // launch scratch shared by the paths
     epp_alloc_t alloc = {nullptr, nullptr, nullptr};
     ~epp_paths() {
         for (size_t i = 0; i < path.size(); ++i) {

@@ -399,7 +399,12 @@ int epp_build_partition(epp_path* p, int F, int gs, const unsigned int* hot_bitm
     EPP_TRY(q->tgt.alloc((size_t)n_vrows * 4, al));
     EPP_TRY(q->mvert.alloc((size_t)M * 4, al));
     EPP_TRY(q->mptr.alloc((size_t)(M + 1) * 4, al));
-    EPP_TRY(q->vpart.alloc((size_t)n_slots * (size_t)F * 4, al));
+    {   // the partial rows live in the scratch the handle's paths share
+        void* scratch = nullptr;
+        EPP_TRY(p->pool->get((size_t)n_slots * (size_t)F * 4, al, &scratch));
+        if (!p->pool->accounted_by) p->pool->accounted_by = p;
+        q->vpart = static_cast<float*>(scratch);
+    }
     // the scan left mptr[0 .. M-1]; its last element is the total
     EPP_HIP_TRY(hipMemcpyAsync(q->mptr.p, mptr_tmp.p, (size_t)M * 4, hipMemcpyDeviceToDevice, s));
     EPP_HIP_TRY(hipMemcpyAsync(q->mptr.as<int32_t>() + M, d_tot + 4, 4, hipMemcpyDeviceToDevice, s));  // (little endian)

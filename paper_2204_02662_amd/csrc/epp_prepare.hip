@@ -645,6 +645,7 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
         built.push_back(p);
         p->n = n;
         p->alloc = P->alloc;
+        p->pool = &P->pool;
         p->n_src = P->set_size[k];
         long long* d_total = dev_total.as<long long>();
         int* d_err = reinterpret_cast<int*>(d_total + 2);
@@ -885,6 +886,7 @@ extern "C" int epp_paths_import(int64_t n, int L, const int32_t* train_ids, int6
         P->path[l] = p;
         p->n = n;
         p->alloc = P->alloc;
+        p->pool = &P->pool;
         p->n_rows = p->n_stream_rows = a.n_rows;
         p->nnz = a.nnz;
         p->n_src = P->set_size[k];

@@ -327,6 +327,7 @@ int epp_prepare_small(const epp_csr_t* g, const int32_t* train_ids, int64_t n_tr
         P->path[l] = p;
         p->n = n;
         p->alloc = P->alloc;
+        p->pool = &P->pool;
         p->n_src = P->set_size[k];
         p->nnz = res[0];
         p->n_rows = p->n_stream_rows = res[1];
