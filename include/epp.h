@@ -16,6 +16,8 @@
  *   EPP_TUNE_PART         source-partitioned layout: 0 never, 1 where it pays, 2 always  [1]
  *   EPP_TUNE_PART_KB      L2 kilobytes per XCD given to the most referenced source rows  [3584]
  *   EPP_TUNE_PART_MINLEN  shortest row that is cut into per-XCD sections                 [96]
+ *   EPP_TUNE_KEEP_CANONICAL  1: a path keeps its canonical entry array beside the source-partitioned
+ *                         copy (otherwise it is given back and rebuilt when export or a new width needs it) [0]
  * None of them changes a result beyond the order of floating-point additions.
  *
  * Notation (paper, Table 1 / Sec. 3 / Sec. 4): V_t training set; N^k the k-neighbour set

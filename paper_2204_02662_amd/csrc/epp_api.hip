@@ -27,6 +27,7 @@ Schedule* find_schedule(epp_path* p, int gs) {
 int prepare_width(epp_path* p, int F, hipStream_t s, epp_path::WidthCfg** out) {
     epp_path::WidthCfg* w = width_cfg(p, F);
     if (!w->sched) {
+        EPP_TRY(epp_ensure_canonical(p, s));  // (given back while all widths ran on reconstructed copies)
         const int gs = w->forced_gs > 0 ? w->forced_gs : epp_default_group_size(p, F);
         Schedule* sc = find_schedule(p, gs);
         if (!sc) EPP_TRY(epp_build_schedule(p, gs, s, &sc));
@@ -37,6 +38,8 @@ int prepare_width(epp_path* p, int F, hipStream_t s, epp_path::WidthCfg** out) {
         // layout (the all-active handle also serves the if-else baseline, which never does)
         if (!w->part || p->all_rows) EPP_TRY(sc->ensure_pieces(F, epp_alloc_of(p)));
         w->sched = sc;
+        EPP_HIP_TRY(hipStreamSynchronize(s));
+        epp_release_canonical_if_unused(p);
     }
     p->last_F = F;
     if (out) *out = w;
@@ -130,6 +133,8 @@ extern "C" int epp_paper_linreg_group_size(int64_t vertices, int64_t undirected_
 extern "C" int epp_path_set_group_size(epp_path_t* p, int F, int gs, epp_stream_t stream) {
     if (!p) { epp_set_error("path is NULL"); return EPP_ERR_INVALID_ARG; }
     if (F < 1) { epp_set_error("F must be >= 1"); return EPP_ERR_INVALID_ARG; }
+    EPP_TRY(epp_ensure_canonical(p, (hipStream_t)stream));  // before the copy it would be rebuilt from goes
+    EPP_HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
     epp_path::WidthCfg* w = width_cfg(p, F);
     w->forced_gs = gs > 0 ? gs : 0;
     if (w->sched) w->sched->drop_pieces(F);  // a table shared with other widths keeps theirs

@@ -189,12 +189,21 @@ struct Partition {
     DevBuf mptr;       // int32[n_split + 1] its slots in vpart
     int64_t n_split = 0, n_slots = 0;
     float* vpart = nullptr;  // float[n_slots][F], in the handle's scratch pool
+    // what is needed to put the entries back into canonical order (the path may give its canonical
+    // entry array back while every prepared width runs on a reconstructed copy)
+    DevBuf srow, tile_first, tile_row;  // cut rows, their first tile, the row of every tile
+    DevBuf toff;       // int32[9 * n_tiles] place of every tile in every section
+    DevBuf sec4;       // section of every entry of the cut rows, 4 bits each, rows byte-aligned
+    DevBuf sec_off;    // int32[n_split] first byte of a cut row in sec4
+    DevBuf whole_off;  // int32[rows] place of a row that is not cut (-1: cut)
+    int64_t n_tiles = 0;
     int sec_g[10] = {};    // first group of every section, then n_groups
     int64_t hot_entries = 0;  // entries in the eight hot sections
     Schedule* sched = nullptr;  // groups over (vptr, cv2)
     ~Partition() { delete sched; }
     size_t bytes() const {
-        return cv2.bytes + vptr.bytes + tgt.bytes + mvert.bytes + mptr.bytes + (sched ? sched->bytes() : 0);
+        return cv2.bytes + vptr.bytes + tgt.bytes + mvert.bytes + mptr.bytes + srow.bytes + tile_first.bytes +
+               tile_row.bytes + toff.bytes + sec4.bytes + sec_off.bytes + whole_off.bytes + (sched ? sched->bytes() : 0);
     }
 };
 
@@ -287,6 +296,11 @@ int epp_tune_locality(epp_path* p, int F, int gs, hipStream_t s, int* log2_slice
 int epp_partition_hot_rows(int F);  // source rows of width F the eight L2s hold together
 // source-partitioned layout of `p` for width F and group size gs, or *out = NULL where it does not pay
 int epp_build_partition(epp_path* p, int F, int gs, const unsigned int* hot_bitmap, hipStream_t s, Partition** out);
+
+// partition.hip: canonical entry array of `p` rebuilt from a reconstructed copy, if it was given back
+int epp_ensure_canonical(epp_path* p, hipStream_t s);
+// gives the canonical entry array back if every prepared width runs on a reconstructed copy
+void epp_release_canonical_if_unused(epp_path* p);
 
 // prepare.hip: exclusive scan of n ints (*total, device, receives the sum); tmp: epp_scan_tmp_bytes(n)
 size_t epp_scan_tmp_bytes(int64_t n);

@@ -79,11 +79,13 @@ __global__ __launch_bounds__(kBlock) void k_part_list_rows(const int* __restrict
 // Tiles of the cut rows: tile_row[t] = m for the tiles of row m (tile_first = scan of the tile counts).
 __global__ __launch_bounds__(kBlock) void k_part_tiles_per_row(const int32_t* __restrict__ rowptr,
                                                                const int32_t* __restrict__ srow, int64_t M,
-                                                               int* __restrict__ ntiles) {
+                                                               int* __restrict__ ntiles, int* __restrict__ nbytes) {
     const int64_t m = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (m >= M) return;
     const int32_t r = srow[m];
-    ntiles[m] = (rowptr[r + 1] - rowptr[r] + kTile - 1) / kTile;
+    const int len = rowptr[r + 1] - rowptr[r];
+    ntiles[m] = (len + kTile - 1) / kTile;
+    nbytes[m] = (len + 1) / 2;  // one 4-bit section id per entry, the row starts on a byte
 }
 
 __global__ __launch_bounds__(kBlock) void k_part_tile_rows(const int* __restrict__ tile_first, const int* __restrict__ ntiles,
@@ -215,7 +217,9 @@ __global__ __launch_bounds__(kBlock) void k_part_scatter_cut(const int2v* __rest
                                                              const int* __restrict__ tile_first, int64_t M, int64_t T,
                                                              const unsigned int* __restrict__ hot,
                                                              const int* __restrict__ toff, const int* __restrict__ voff,
-                                                             const int* __restrict__ klen, int2v* __restrict__ cv2) {
+                                                             const int* __restrict__ klen, int2v* __restrict__ cv2,
+                                                             const int* __restrict__ sec_off,
+                                                             unsigned char* __restrict__ sec4) {
     const int64_t t = (int64_t)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
     if (t >= T) return;
     const int lane = lane_id();
@@ -261,17 +265,82 @@ __global__ __launch_bounds__(kBlock) void k_part_scatter_cut(const int2v* __rest
             e.x = (e.x & kColMask) | (sec[i] == kHot ? (e.x & kCold) : 0) | (last ? kRowEnd : 0);
             cv2[dest] = e;
         }
+        // the section ids, two to a byte (an even lane writes its own and its neighbour's): they are
+        // what puts the entries back into the row's order later
+        const int mine = sec[i] & 15;  // (-1 beyond the row's end -> 15, never read)
+        const int both = mine | (__shfl_down(mine, 1, 64) << 4);
+        const int j = (int)(t - tile_first[m]) * kTile + i * 64 + lane;  // entry index within the row
+        if ((lane & 1) == 0 && p0 + i * 64 + lane < p1) sec4[sec_off[m] + (j >> 1)] = (unsigned char)both;
     }
+}
+
+// The reverse: the entries of the cut rows back in their rows' order (canonical entry array), from
+// the recorded section ids; flags as the canonical array carries them (row end on the row's last
+// entry; the streamed-source mark survives in the last section only, and hot sources never carry it).
+__global__ __launch_bounds__(kBlock) void k_part_gather_cut(const int2v* __restrict__ cv2,
+                                                            const int32_t* __restrict__ rowptr,
+                                                            const int32_t* __restrict__ srow,
+                                                            const int32_t* __restrict__ tile_row,
+                                                            const int* __restrict__ tile_first, int64_t T,
+                                                            const int* __restrict__ toff, const int* __restrict__ sec_off,
+                                                            const unsigned char* __restrict__ sec4,
+                                                            int2v* __restrict__ cv) {
+    const int64_t t = (int64_t)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
+    if (t >= T) return;
+    const int lane = lane_id();
+    const int32_t m = tile_row[t], r = srow[m];
+    const int p0 = rowptr[r] + (int)(t - tile_first[m]) * kTile, row_end = rowptr[r + 1], p1 = min(p0 + kTile, row_end);
+    int next[kSec];
+    {
+        const int b = lane < kSec ? toff[lane * T + t] : 0;
+#pragma unroll
+        for (int x = 0; x < kSec; ++x) next[x] = __shfl(b, x, 64);
+    }
+    const unsigned char* __restrict__ ids = sec4 + sec_off[m] + ((int)(t - tile_first[m]) * kTile >> 1);
+#pragma unroll 4
+    for (int i = 0; i < kTile / 64; ++i) {
+        const int j = p0 + i * 64 + lane;
+        int sec = -1;
+        if (j < p1) sec = (ids[(i * 64 + lane) >> 1] >> ((lane & 1) * 4)) & 15;
+        int src = 0;
+#pragma unroll
+        for (int x = 0; x < kSec; ++x) {
+            const unsigned long long mask = __ballot(sec == x);
+            if (sec == x) src = next[x] + __popcll(mask & low_mask(lane));
+            next[x] += __popcll(mask);
+        }
+        if (sec >= 0) {
+            int2v e = cv2[src];
+            e.x = (e.x & ~kRowEnd) | (j == row_end - 1 ? kRowEnd : 0);
+            cv[j] = e;
+        }
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_part_gather_whole(const int2v* __restrict__ cv2,
+                                                              const int32_t* __restrict__ rowptr, int64_t R,
+                                                              const int* __restrict__ whole_off, int2v* __restrict__ cv) {
+    const int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (r >= R || whole_off[r] < 0) return;
+    const int p0 = rowptr[r], p1 = rowptr[r + 1];
+    const int2v* __restrict__ src = cv2 + whole_off[r];
+    for (int j = p0; j < p1; ++j) cv[j] = src[j - p0];
 }
 
 // Rows that are not cut: copied as they are (flags included) to their place at the end of the last section.
 __global__ __launch_bounds__(kBlock) void k_part_scatter_whole(const int2v* __restrict__ cv,
                                                                const int32_t* __restrict__ rowptr, int64_t R, int64_t M,
                                                                const int32_t* __restrict__ m_of_row,
-                                                               const int* __restrict__ voff, int2v* __restrict__ cv2) {
+                                                               const int* __restrict__ voff, int2v* __restrict__ cv2,
+                                                               int* __restrict__ whole_off) {
     const int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (r >= R || m_of_row[r] >= 0) return;
+    if (r >= R) return;
+    if (m_of_row[r] >= 0) {
+        whole_off[r] = -1;
+        return;
+    }
     const int p0 = rowptr[r], p1 = rowptr[r + 1];
+    whole_off[r] = voff[kSec * M + r];
     int2v* __restrict__ d = cv2 + voff[kSec * M + r];
     for (int j = p0; j < p1; ++j) d[j - p0] = cv[j];
 }
@@ -310,7 +379,8 @@ int epp_build_partition(epp_path* p, int F, int gs, const unsigned int* hot_bitm
     a1.take(&midx, (size_t)R * 4);
     a1.take(&m_of_row, (size_t)R * 4);
     a1.take(&scan_tmp, epp_scan_tmp_bytes(R));
-    // [0] cut rows, [1] tiles, [2] entries of cut rows, [3] hot entries, [4] partial rows, [5] all entries, [6] virtual rows
+    // [0] cut rows, [1] tiles, [2] entries of cut rows, [3] hot entries, [4] partial rows, [5] all entries,
+    // [6] virtual rows, [7] bytes of the recorded section ids
     a1.take(&totals, 8 * sizeof(long long));
     EPP_HIP_TRY(hipMemsetAsync(totals.p, 0, totals.bytes, s));
     long long* d_tot = totals.as<long long>();
@@ -325,22 +395,26 @@ int epp_build_partition(epp_path* p, int F, int gs, const unsigned int* hot_bitm
 
     // ---- tiles of the cut rows
     DevArena a2;
-    DevBuf srow, ntiles, tile_first, npieces, mptr_tmp;
-    EPP_TRY(a2.reserve(5 * DevArena::rounded((size_t)(M + 1) * 4), al));
+    DevBuf srow, ntiles, tile_first, npieces, mptr_tmp, nbytes, sec_off;
+    EPP_TRY(a2.reserve(7 * DevArena::rounded((size_t)(M + 1) * 4), al));
     a2.take(&srow, (size_t)M * 4);
     a2.take(&ntiles, (size_t)M * 4);
     a2.take(&tile_first, (size_t)M * 4);
     a2.take(&npieces, (size_t)M * 4);
     a2.take(&mptr_tmp, (size_t)(M + 1) * 4);
+    a2.take(&nbytes, (size_t)M * 4);
+    a2.take(&sec_off, (size_t)M * 4);
     hipLaunchKernelGGL(k_part_list_rows, dim3(grid_for(R, kBlock)), dim3(kBlock), 0, s, flag.as<int>(), midx.as<int>(), R,
                        srow.as<int32_t>(), m_of_row.as<int32_t>());
     hipLaunchKernelGGL(k_part_tiles_per_row, dim3(grid_for(M, kBlock)), dim3(kBlock), 0, s, rowptr, srow.as<int32_t>(), M,
-                       ntiles.as<int>());
+                       ntiles.as<int>(), nbytes.as<int>());
     epp_scan_exclusive(ntiles.as<int>(), tile_first.as<int>(), M, d_tot + 1, scan_tmp.as<int>(), s);
+    epp_scan_exclusive(nbytes.as<int>(), sec_off.as<int>(), M, d_tot + 7, scan_tmp.as<int>(), s);
     EPP_HIP_TRY(hipGetLastError());
     EPP_HIP_TRY(hipMemcpyAsync(h_tot + 1, d_tot + 1, sizeof(long long), hipMemcpyDeviceToHost, s));
+    EPP_HIP_TRY(hipMemcpyAsync(h_tot + 7, d_tot + 7, sizeof(long long), hipMemcpyDeviceToHost, s));
     EPP_HIP_TRY(hipStreamSynchronize(s));
-    const int64_t T = h_tot[1];
+    const int64_t T = h_tot[1], sec_bytes = h_tot[7];
 
     // ---- entries per (section, tile), their places, the keys; is it worth it?
     const int64_t K = kSec * M + R;
@@ -399,6 +473,20 @@ int epp_build_partition(epp_path* p, int F, int gs, const unsigned int* hot_bitm
     EPP_TRY(q->tgt.alloc((size_t)n_vrows * 4, al));
     EPP_TRY(q->mvert.alloc((size_t)M * 4, al));
     EPP_TRY(q->mptr.alloc((size_t)(M + 1) * 4, al));
+    // kept for putting the entries back into canonical order
+    q->n_tiles = T;
+    EPP_TRY(q->srow.alloc((size_t)M * 4, al));
+    EPP_TRY(q->tile_first.alloc((size_t)M * 4, al));
+    EPP_TRY(q->sec_off.alloc((size_t)M * 4, al));
+    EPP_TRY(q->tile_row.alloc((size_t)T * 4, al));
+    EPP_TRY(q->toff.alloc((size_t)kSec * T * 4, al));
+    EPP_TRY(q->sec4.alloc((size_t)sec_bytes, al));
+    EPP_TRY(q->whole_off.alloc((size_t)R * 4, al));
+    EPP_HIP_TRY(hipMemcpyAsync(q->srow.p, srow.p, (size_t)M * 4, hipMemcpyDeviceToDevice, s));
+    EPP_HIP_TRY(hipMemcpyAsync(q->tile_first.p, tile_first.p, (size_t)M * 4, hipMemcpyDeviceToDevice, s));
+    EPP_HIP_TRY(hipMemcpyAsync(q->sec_off.p, sec_off.p, (size_t)M * 4, hipMemcpyDeviceToDevice, s));
+    EPP_HIP_TRY(hipMemcpyAsync(q->tile_row.p, tile_row.p, (size_t)T * 4, hipMemcpyDeviceToDevice, s));
+    EPP_HIP_TRY(hipMemcpyAsync(q->toff.p, toff.p, (size_t)kSec * T * 4, hipMemcpyDeviceToDevice, s));
     {   // the partial rows live in the scratch the handle's paths share
         void* scratch = nullptr;
         EPP_TRY(p->pool->get((size_t)n_slots * (size_t)F * 4, al, &scratch));
@@ -415,9 +503,11 @@ int epp_build_partition(epp_path* p, int F, int gs, const unsigned int* hot_bitm
                        sec_start.as<int>());
     hipLaunchKernelGGL(k_part_scatter_cut, dim3(grid_for(T, kBlock / 64)), dim3(kBlock), 0, s, cv, rowptr,
                        srow.as<int32_t>(), tile_row.as<int32_t>(), tile_first.as<int>(), M, T, hot_bitmap, toff.as<int>(),
-                       voff.as<int>(), klen.as<int>(), reinterpret_cast<int2v*>(q->cv2.p));
+                       voff.as<int>(), klen.as<int>(), reinterpret_cast<int2v*>(q->cv2.p), sec_off.as<int>(),
+                       q->sec4.as<unsigned char>());
     hipLaunchKernelGGL(k_part_scatter_whole, dim3(grid_for(R, kBlock)), dim3(kBlock), 0, s, cv, rowptr, R, M,
-                       m_of_row.as<int32_t>(), voff.as<int>(), reinterpret_cast<int2v*>(q->cv2.p));
+                       m_of_row.as<int32_t>(), voff.as<int>(), reinterpret_cast<int2v*>(q->cv2.p),
+                       q->whole_off.as<int>());
     EPP_HIP_TRY(hipGetLastError());
     int h_sec[kSec];
     EPP_HIP_TRY(hipMemcpyAsync(h_sec, sec_start.p, sizeof(h_sec), hipMemcpyDeviceToHost, s));
@@ -428,5 +518,39 @@ int epp_build_partition(epp_path* p, int F, int gs, const unsigned int* hot_bitm
     q->sec_g[kSec] = (int)q->sched->n_groups;
     guard.q = nullptr;
     *out = q;
+    return EPP_OK;
+}
+
+// The canonical entry array of a path is only read when a width is prepared, by launches of a width
+// without a reconstructed copy, and by epp_path_export.  While every prepared width of a path
+// (other than the all-active graph, which also serves the if-else baseline) runs on its reconstructed
+// copy, the canonical array is given back to the allocator; it is rebuilt from a copy, bit for bit,
+// the next time one of those needs it.
+void epp_release_canonical_if_unused(epp_path* p) {
+    const char* e = std::getenv("EPP_TUNE_KEEP_CANONICAL");
+    if (e && e[0] == '1') return;
+    if (p->all_rows || !p->cv.p || !p->cv.owned || p->widths.empty()) return;
+    for (const auto& w : p->widths)
+        if (w.sched && !w.part) return;  // a width that launches on the canonical array
+    bool any = false;
+    for (const auto& w : p->widths) any |= (w.part != nullptr);
+    if (any) p->cv.release();
+}
+
+int epp_ensure_canonical(epp_path* p, hipStream_t s) {
+    if (p->cv.p || p->nnz == 0) return EPP_OK;
+    const Partition* q = nullptr;
+    for (const auto& w : p->widths)
+        if (w.part) q = w.part;
+    if (!q) { epp_set_error("the path has no entry array"); return EPP_ERR_INVALID_ARG; }
+    EPP_TRY(p->cv.alloc((size_t)p->nnz * 8, epp_alloc_of(p)));
+    const int2v* cv2 = reinterpret_cast<const int2v*>(q->cv2.p);
+    int2v* cv = reinterpret_cast<int2v*>(p->cv.p);
+    hipLaunchKernelGGL(k_part_gather_cut, dim3(grid_for(q->n_tiles, kBlock / 64)), dim3(kBlock), 0, s, cv2,
+                       p->rowptr.as<int32_t>(), q->srow.as<int32_t>(), q->tile_row.as<int32_t>(), q->tile_first.as<int>(),
+                       q->n_tiles, q->toff.as<int>(), q->sec_off.as<int>(), q->sec4.as<unsigned char>(), cv);
+    hipLaunchKernelGGL(k_part_gather_whole, dim3(grid_for(p->n_stream_rows, kBlock)), dim3(kBlock), 0, s, cv2,
+                       p->rowptr.as<int32_t>(), p->n_stream_rows, q->whole_off.as<int>(), cv);
+    EPP_HIP_TRY(hipGetLastError());
     return EPP_OK;
 }

@@ -687,13 +687,14 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
         p->n_rows = R;
         p->n_stream_rows = R;  // every row of a path has at least one entry
         P->set_size[k + 1] = R;
-        // entries | row ids | row pointer, each 256-byte aligned
+        // the entries in an allocation of their own (it can be given back once every prepared width
+        // runs on a reconstructed copy); row ids | row pointer together, each 256-byte aligned
         const size_t cv_bytes = (size_t)kept * sizeof(int2), ids_bytes = (size_t)R * 4, ptr_bytes = (size_t)(R + 1) * 4;
-        EPP_TRY(p->store.alloc(DevArena::rounded(cv_bytes) + DevArena::rounded(ids_bytes) + DevArena::rounded(ptr_bytes), al));
+        EPP_TRY(p->cv.alloc(cv_bytes, al));
+        EPP_TRY(p->store.alloc(DevArena::rounded(ids_bytes) + DevArena::rounded(ptr_bytes), al));
         char* base = p->store.as<char>();
-        p->cv.view(base, cv_bytes);
-        p->row_ids.view(base + DevArena::rounded(cv_bytes), ids_bytes);
-        p->rowptr.view(base + DevArena::rounded(cv_bytes) + DevArena::rounded(ids_bytes), ptr_bytes);
+        p->row_ids.view(base, ids_bytes);
+        p->rowptr.view(base + DevArena::rounded(ids_bytes), ptr_bytes);
         if (edge_tiles) {
             hipLaunchKernelGGL(k_edge_extract, dim3(edge_tiles), dim3(kBlock), 0, s, g->col, g->val, n_seg,
                                mask.as<unsigned long long>(), seg_base.as<int>(), p->cv.as<int2>());
@@ -936,6 +937,7 @@ extern "C" int epp_path_export(const epp_path_t* p, int32_t* row_ids, int32_t* r
         EPP_HIP_TRY(hipMemcpyAsync(rowptr, ptr, (size_t)(p->n_rows + 1) * 4, hipMemcpyDeviceToDevice, s));
     }
     if ((col || val) && p->nnz > 0) {
+        EPP_TRY(epp_ensure_canonical(const_cast<epp_path*>(p), s));
         hipLaunchKernelGGL(k_deinterleave, dim3(grid_for(p->nnz, kBlock)), dim3(kBlock), 0, s, p->cv.as<int2>(), p->nnz,
                            col, val);
     }

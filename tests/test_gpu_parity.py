@@ -372,6 +372,41 @@ def test_source_partitioned_layout_on_every_row(monkeypatch, F, min_len):
     assert_close(got[rows], oracle.path_aggregate(g.n, paths_o[0], Xl)[rows], f"if-else beside the partition F={F}")
 
 
+def test_canonical_entries_are_given_back_and_rebuilt(monkeypatch):
+    """While every prepared width of a path runs on its source-partitioned copy the canonical
+    entry array is not kept; export, a further width without such a copy, and a new group size
+    rebuild it from the copy bit for bit (the recorded section ids put every entry back in its
+    row's order)."""
+    g = graphgen.random_graph("rmat", 30_000, seed=271, raw_draws=400_000)
+    train = graphgen.training_set(g.n, 3000, 272)
+    sets_o, paths_o = oprep(g, train, 2)
+    monkeypatch.setenv("EPP_TUNE_PART", "2")
+    monkeypatch.setenv("EPP_TUNE_PART_KB", "64")
+    monkeypatch.setenv("EPP_TUNE_PART_MINLEN", "8")
+    held = {}
+    for keep in ("1", "0"):
+        monkeypatch.setenv("EPP_TUNE_KEEP_CANONICAL", keep)
+        paths = gpu_prepare(g, train, 2)
+        p = paths.path(0)
+        X = graphgen.normal_rows(g.n, 128, sets_o[1], 281)
+        want = oracle.path_aggregate(g.n, paths_o[0], X)
+        assert_close(run_partial(p, X), want, f"keep={keep} F=128")
+        assert p.info().part_rows > 0
+        held[keep] = p.info().bytes
+        if keep == "0":
+            assert held["0"] <= held["1"] - 8 * p.info().nnz  # the canonical entries are not held
+        assert_paths_bit_exact(paths, sets_o, paths_o, 2)  # export rebuilds them
+        monkeypatch.setenv("EPP_TUNE_PART", "1")  # a narrow width never gets a partitioned copy by itself
+        X16 = graphgen.normal_rows(g.n, 16, sets_o[1], 282)
+        assert_close(run_partial(p, X16), oracle.path_aggregate(g.n, paths_o[0], X16), f"keep={keep} F=16 after F=128")
+        assert p.info().part_rows == 0 and p.info().bytes >= held["1"] - (1 << 20)  # now it is needed, and stays
+        assert_close(run_partial(p, X), want, f"keep={keep} F=128 again")
+        monkeypatch.setenv("EPP_TUNE_PART", "2")
+        p.set_group_size(128, 48)
+        assert_close(run_partial(p, X), want, f"keep={keep} F=128 gs=48")
+        assert_paths_bit_exact(paths, sets_o, paths_o, 2)
+
+
 def test_marks_of_a_path_do_not_depend_on_the_order_of_its_widths(monkeypatch):
     """One path used at two widths: the streamed-source marks are those of the wider width,
     whichever was prepared first, and results stay within tolerance either way."""
