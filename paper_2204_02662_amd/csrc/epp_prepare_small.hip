@@ -226,14 +226,14 @@ __global__ __launch_bounds__(kThreads) void k_prepare_small(SmallArgs a) {
     }
 }
 
-// Pinned host words for the read-back, one buffer per host thread, kept for the thread's life.
+// Pinned host words for the read-back, one buffer per host thread, kept until the process ends (a
+// few kilobytes; freeing them from a thread-exit handler could run after the HIP runtime is gone).
 struct PinnedWords {
     long long* p = nullptr;
     size_t count = 0;
-    ~PinnedWords() { if (p) (void)hipHostFree(p); }
     long long* get(size_t need) {
         if (count < need) {
-            if (p) (void)hipHostFree(p);
+            if (p) (void)hipHostFree(p);  // (grown while the runtime is certainly alive)
             p = nullptr;
             count = 0;
             if (hipHostMalloc((void**)&p, need * sizeof(long long), hipHostMallocDefault) != hipSuccess) {

@@ -359,6 +359,25 @@ def test_source_partitioned_layout_on_every_row(monkeypatch, F, min_len):
         Xp[sets_o[2 - l - 1] == 0] = np.nan
         assert_close(run_partial(p, Xp), want, f"partitioned F={F} l={l} gs={gs}, nan-poison")
     assert_paths_bit_exact(paths, sets_o, paths_o, 2)  # the canonical form is not touched
+    # the three kernels of a partitioned launch captured in a HIP graph: replays reproduce the eager result
+    p = paths.path(0)
+    p.prepare_width(F)
+    gin = torch.from_numpy(graphgen.normal_rows(g.n, F, sets_o[1], 273)).to(dev())
+    gout = torch.zeros_like(gin)
+    epp.epp_backward_aggregate(p, gin, gout)
+    torch.cuda.synchronize()
+    eager = gout.clone()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        epp.epp_backward_aggregate(p, gin, gout)
+    for rep in range(3):
+        gout.normal_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        rows_t = torch.from_numpy(sets_o[2].astype(bool)).to(dev())
+        assert torch.equal(gout[rows_t], eager[rows_t]), f"replay {rep}"
+    del graph
     full = gpu_prepare_full(g)
     X = graphgen.normal_rows(g.n, F, None, 279)
     got = run_full(full, X)
