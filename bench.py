@@ -257,6 +257,9 @@ def run_config(config_id: int, args, detail: bool):
         layers.append({
             "l": l, "F": F, "rows": i.n_rows, "sources": i.n_src, "nnz": i.nnz, "max_len": i.max_len,
             "group_size": i.group_size, "groups": i.n_groups, "split_rows": i.n_split_rows,
+            # source-partitioned layout (zeros: not in use for this layer)
+            "partitioned_rows": i.part_rows, "entries_in_xcd_sections": i.part_hot_entries,
+            "partial_rows": i.part_partial_rows,
             "ms": ms, "ms_median": layer_spread[l][0], "ms_min": layer_spread[l][1], "algorithmic_bytes": bmin,
             "roofline_GBs": bmin / ms / 1e6 if ms > 0 else None,
             "roofline_frac": bmin / ms / 1e6 / HBM_PEAK_GBS if ms > 0 else None,
