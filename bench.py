@@ -265,7 +265,9 @@ def run_config(config_id: int, args, detail: bool):
             "roofline_frac": bmin / ms / 1e6 / HBM_PEAK_GBS if ms > 0 else None,
             "gather_GBs": bedge / ms / 1e6 if ms > 0 else None,
         })
-    dom = max(layers, key=lambda d: d["ms"])
+    # the dominant launch: the layer with the most work (entries x width); by time the two widest layers of a
+    # deep configuration are within a per cent of each other and would swap from run to run
+    dom = max(layers, key=lambda d: (d["nnz"] * d["F"], d["ms"]))
     traffic, l2_hit = read_traffic(cfg.name).get(dom["l"], (None, None)) if detail else (None, None)
     lines = dom["nnz"] * ((dom["F"] * 4 + 127) // 128)
     model_ms = (lines * ((1.0 - l2_hit) / GATHER_MISS_LINES_PER_S + l2_hit / GATHER_L2_LINES_PER_S) * 1e3
@@ -412,7 +414,7 @@ def run_config(config_id: int, args, detail: bool):
 
 def compact(r):
     """What the headline line keeps of a side configuration."""
-    dom = max(r["partially_active"]["layers"], key=lambda d: d["ms"])
+    dom = max(r["partially_active"]["layers"], key=lambda d: (d["nnz"] * d["F"], d["ms"]))
     out = {
         "workload": r["config"]["workload"], "n": r["config"]["n"], "nnz": r["config"]["nnz"], "L": r["config"]["L"],
         "widths_l0_first": r["config"]["widths_l0_first"], "n_train": r["config"]["n_train"],
