@@ -260,6 +260,8 @@ def run_config(config_id: int, args, detail: bool):
             # source-partitioned layout (zeros: not in use for this layer)
             "partitioned_rows": i.part_rows, "entries_in_xcd_sections": i.part_hot_entries,
             "partial_rows": i.part_partial_rows,
+            # 1: the path keeps no entry arrays and runs on those of layer l - 1 (skipping that path's extra entries)
+            "runs_on_entries_of_outer_path": i.shares_entries,
             "ms": ms, "ms_median": layer_spread[l][0], "ms_min": layer_spread[l][1], "algorithmic_bytes": bmin,
             "roofline_GBs": bmin / ms / 1e6 if ms > 0 else None,
             "roofline_frac": bmin / ms / 1e6 / HBM_PEAK_GBS if ms > 0 else None,

@@ -16,6 +16,8 @@
  *   EPP_TUNE_PART         source-partitioned layout: 0 never, 1 where it pays, 2 always  [1]
  *   EPP_TUNE_PART_KB      L2 kilobytes per XCD given to the most referenced source rows  [3584]
  *   EPP_TUNE_PART_MINLEN  shortest row that is cut into per-XCD sections                 [96]
+ *   EPP_TUNE_SHARE_PCT    a path runs on the arrays of the next outer path (no entry arrays of its own) if it
+ *                         holds at least this percentage of that path's entries; 0: never     [95]
  *   EPP_TUNE_KEEP_CANONICAL  1: a path keeps its canonical entry array beside the source-partitioned
  *                         copy (otherwise it is given back and rebuilt when export or a new width needs it) [0]
  * None of them changes a result beyond the order of floating-point additions.
@@ -38,7 +40,7 @@ extern "C" {
 #define EPP_OK 0
 #define EPP_ERR_INVALID_ARG (-1)     /* NULL pointer, L < 1, F < 1, negative size ...       */
 #define EPP_ERR_OUT_OF_RANGE_ID (-2) /* a training id outside [0, n)                        */
-#define EPP_ERR_TOO_LARGE (-3)       /* n >= 2^30 or nnz >= 2^31                            */
+#define EPP_ERR_TOO_LARGE (-3)       /* n >= 2^29 or nnz >= 2^31                            */
 #define EPP_ERR_ALLOC (-4)           /* device or host allocation failed                    */
 #define EPP_ERR_HIP (-5)             /* a HIP runtime call failed (message has the detail)  */
 
@@ -71,7 +73,7 @@ typedef struct {
  * the library only relies on the order being the caller's canonical one and preserves it).
  * Self-loops are not added: whatever is stored is the operator. */
 typedef struct {
-    int64_t n;             /* number of vertices, < 2^30                        */
+    int64_t n;             /* number of vertices, < 2^29                        */
     int64_t nnz;           /* number of stored entries, < 2^31                  */
     const int32_t* rowptr; /* device, n + 1 entries, rowptr[0] = 0              */
     const int32_t* col;    /* device, nnz entries, each in [0, n)               */
@@ -100,6 +102,11 @@ typedef struct {
     int64_t part_rows;          /* rows cut into per-section shares                          */
     int64_t part_hot_entries;   /* entries in the eight XCD sections                         */
     int64_t part_partial_rows;  /* partial rows of F floats written and added up per launch  */
+    /* 1: the path keeps no entry arrays of its own and runs on those of the next outer path (path
+       l - 1), skipping that path's extra entries (Sec. 4: the paths of consecutive layers overlap
+       almost entirely once the active sets saturate).  The schedule fields above then describe the
+       outer path's tables; `bytes` counts only what this path holds itself. */
+    int32_t shares_entries;
 } epp_path_info_t;
 
 /* Execution path preparing (Sec. 4): computes N^k for k = 0..L (Theorem 1) by backward
@@ -111,6 +118,9 @@ typedef struct {
  *   alloc      the caller's device allocator, or NULL (see epp_alloc_t)
  *   stream     work is enqueued here; the call synchronises the stream before returning
  *   out        receives a handle owned by the library; release with epp_destroy_paths
+ * Where the active sets are nested (always with self-loops) and the path of layer l holds nearly
+ * all entries of the path of layer l - 1, it is stored as a view of that path: see
+ * epp_path_info_t.shares_entries.  The exported canonical form is the same either way.
  * n_train = 0 is valid (all paths empty).  Any training id or column id outside [0, n):
  * EPP_ERR_OUT_OF_RANGE_ID; a row pointer that does not rise from 0 to nnz: EPP_ERR_INVALID_ARG
  * (both are checked on the GPU as part of the first pass; neither can make a kernel fault). */
@@ -170,7 +180,9 @@ int epp_path_prepare_width(epp_path_t* p, int F, epp_stream_t stream);
  * Rebuilds the group table: group g holds entries [g*gs, (g+1)*gs) of the edge array, so a
  * row longer than gs is always cut and short rows share a group.  Prepares the width as
  * epp_path_prepare_width does (allocates, synchronises).  The partial rows of the previous
- * table are freed: a HIP graph captured with the old table must not be replayed any more. */
+ * table are freed: a HIP graph captured with the old table must not be replayed any more.
+ * Two paths that share their entries (epp_path_info_t.shares_entries) share their group tables:
+ * the size set through either holds for both. */
 int epp_path_set_group_size(epp_path_t* p, int F, int gs, epp_stream_t stream);
 
 /* Partially-active backward aggregation of one layer (Alg. 2, aggregation loop):

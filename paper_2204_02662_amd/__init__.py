@@ -93,7 +93,7 @@ class _PathInfo(ctypes.Structure):
                 ("bytes", ctypes.c_int64), ("sched_F", ctypes.c_int32), ("group_size", ctypes.c_int32),
                 ("n_groups", ctypes.c_int64), ("n_split_rows", ctypes.c_int64),
                 ("part_rows", ctypes.c_int64), ("part_hot_entries", ctypes.c_int64),
-                ("part_partial_rows", ctypes.c_int64)]
+                ("part_partial_rows", ctypes.c_int64), ("shares_entries", ctypes.c_int32)]
 
 
 _lib = None
@@ -178,6 +178,7 @@ class PathInfo:
     part_rows: int = 0
     part_hot_entries: int = 0
     part_partial_rows: int = 0
+    shares_entries: int = 0
 
 
 class Path_:
@@ -202,7 +203,7 @@ class Path_:
         _check(load_library().epp_path_info(self._h, ctypes.byref(raw)))
         return PathInfo(raw.n, raw.n_rows, raw.nnz, raw.n_src, raw.max_len, list(raw.len_hist), raw.bytes,
                         raw.sched_F, raw.group_size, raw.n_groups, raw.n_split_rows, raw.part_rows,
-                        raw.part_hot_entries, raw.part_partial_rows)
+                        raw.part_hot_entries, raw.part_partial_rows, raw.shares_entries)
 
     def export(self):
         """(row_ids, rowptr, col, val) device tensors in canonical form."""

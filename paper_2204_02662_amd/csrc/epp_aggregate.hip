@@ -31,9 +31,7 @@
 namespace {
 
 constexpr int kBlock = 256;
-constexpr int kRowEnd = (int)0x80000000u;
-constexpr int kCold = 0x40000000;
-constexpr int kColMask = 0x3FFFFFFF;
+constexpr int kRowEnd = kEntRowEnd, kCold = kEntCold, kOuterOnly = kEntOuterOnly, kColMask = kEntCol;
 
 typedef int int2v __attribute__((ext_vector_type(2)));
 typedef float float2v __attribute__((ext_vector_type(2)));
@@ -112,6 +110,9 @@ struct AggArgs {
     int n;                     // a row target t >= n is row t - n of the partial rows of the cut rows
                                // (float[slots][F]); INT_MAX without the partitioned layout
     uintptr_t part_delta;      // address of that array minus address of row n of `out`
+    // launch for the inner path that shares these arrays only: 256 zero bytes, gathered in place of
+    // the source row of an entry that is not the inner path's
+    const float* zero;
 };
 
 template <int VEC>
@@ -143,10 +144,11 @@ __global__ __launch_bounds__(kBlock) void k_combine_cut_rows(const int32_t* __re
     if (k >= n_cut) return;
     const int32_t r = cut_rows[k];
     int32_t v = row_ids ? row_ids[r] : r;
-    if (only_bits && !((only_bits[v >> 5] >> (v & 31)) & 1u)) return;
     if (vpart && v >= n) {  // partitioned layout: the row is one section's share of a vertex's list
         out = vpart;
         v -= n;
+    } else if (only_bits && !((only_bits[v >> 5] >> (v & 31)) & 1u)) {
+        return;  // not a row of this launch (if-else baseline; inner path on shared arrays)
     }
     const int64_t g0 = rowptr[r] / gs, g1 = ((int64_t)rowptr[r + 1] - 1) / gs;
     for (int f = threadIdx.x & (Fp - 1); f < F; f += Fp) {
@@ -170,11 +172,13 @@ __global__ __launch_bounds__(kBlock) void k_combine_cut_rows(const int32_t* __re
 __global__ __launch_bounds__(kBlock) void k_combine_sections(const int32_t* __restrict__ mvert,
                                                              const int32_t* __restrict__ mptr, int64_t n_split, int F,
                                                              int log2Fp, const float* __restrict__ vpart,
+                                                             const unsigned int* __restrict__ only_bits,
                                                              float* __restrict__ out) {
     const int Fp = 1 << log2Fp;
     const int64_t m = ((int64_t)blockIdx.x * kBlock + threadIdx.x) >> log2Fp;
     if (m >= n_split) return;
     const int32_t v = mvert[m];
+    if (only_bits && !((only_bits[v >> 5] >> (v & 31)) & 1u)) return;  // not a row of the inner path
     const int s0 = mptr[m], s1 = mptr[m + 1];
     for (int f = threadIdx.x & (Fp - 1); f < F; f += Fp) {
         float x[9];
@@ -204,9 +208,16 @@ __global__ __launch_bounds__(kBlock) void k_combine_sections(const int32_t* __re
 // PART: the source-partitioned layout (block-to-group mapping by XCD, targets in the array of
 // partial rows).  A variant of its own, so that the plain kernels keep their register budget (the
 // few registers the extra addressing needs cost the 4-byte-lane kernel a wavefront per SIMD).
-template <int VEC, int LOG2T, int U_, bool IFELSE, bool COLD, bool PART>
-__global__ __launch_bounds__(kBlock, IFELSE ? ((COLD && VEC != 1) ? 4 : 5) : 4) void k_aggregate(AggArgs a) {
+//
+// INNER: the launch serves the inner path that shares these entry arrays.  An entry that is not
+// the inner path's (kOuterOnly) is parked with weight zero and gathers from a block of zeros
+// instead of its source row (which the inner layer must not read), so the gathers stay
+// unconditional; a row left without any entry of the inner path is not written, unless its target
+// is a partial row, which the adding kernels always read.
+template <int VEC, int LOG2T, int U_, bool IFELSE, bool COLD, bool PART, bool INNER>
+__global__ __launch_bounds__(kBlock, IFELSE ? ((COLD && VEC != 1) ? 4 : 5) : ((INNER && VEC == 1 && !PART) ? 5 : 4)) void k_aggregate(AggArgs a) {
     static_assert(!(IFELSE && PART), "the if-else baseline walks the graph as it is given");
+    static_assert(!(IFELSE && INNER), "the if-else baseline has its own tests");
     constexpr int T = 1 << LOG2T;
     constexpr int S = 4 * T;              // pairs staged per slot
     constexpr int U = U_ < S ? U_ : S;    // S is a multiple of U
@@ -283,6 +294,7 @@ __global__ __launch_bounds__(kBlock, IFELSE ? ((COLD && VEC != 1) ? 4 : 5) : 4) 
 #pragma unroll
         for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
         bool open = false;  // acc holds entries of a row whose end has not been met
+        bool any = false;   // INNER: the current row has an entry of the inner path (in this group)
         for (int base = 0; base < len; base += S) {
             if constexpr (IFELSE) {
                 // "is this neighbour active" test of selective scheduling, done for the 4T pairs
@@ -301,7 +313,12 @@ __global__ __launch_bounds__(kBlock, IFELSE ? ((COLD && VEC != 1) ? 4 : 5) : 4) 
             __builtin_amdgcn_wave_barrier();
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                if (base + i * T + t >= len) { pre[i].x &= kColMask; pre[i].y = 0; }  // no row end, weight 0
+                if constexpr (INNER) {
+                    if (base + i * T + t >= len) pre[i] = int2v{kOuterOnly, 0};
+                    else if (pre[i].x & kOuterOnly) { pre[i].x &= ~kCold; pre[i].y = 0; }
+                } else {
+                    if (base + i * T + t >= len) { pre[i].x &= kColMask; pre[i].y = 0; }  // no row end, weight 0
+                }
                 stage[i * T + t] = pre[i];
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -331,6 +348,7 @@ __global__ __launch_bounds__(kBlock, IFELSE ? ((COLD && VEC != 1) ? 4 : 5) : 4) 
                     if (act[u]) {
                         const int c = e[u].x & kColMask;
                         gvec_ptr p = (gvec_ptr)(src + (size_t)c * (size_t)a.F);
+                        if constexpr (INNER) p = (e[u].x & kOuterOnly) ? (gvec_ptr)a.zero : p;
                         if (COLD && (e[u].x & kCold)) {
                             // rarely referenced source: streamed, so that it does not evict hot rows from
                             // L2 and the memory-side cache.  (The address is laundered, and the branch
@@ -356,9 +374,11 @@ __global__ __launch_bounds__(kBlock, IFELSE ? ((COLD && VEC != 1) ? 4 : 5) : 4) 
                     }
                     const int j = base + b + u;
                     if (j < len) open = true;
+                    if constexpr (INNER) any |= !(e[u].x & kOuterOnly);
                     if (e[u].x < 0) {  // last entry of row r
                         bool wr = fok;
                         if constexpr (IFELSE) wr = fok && ((a.row_bits[v >> 5] >> (v & 31)) & 1u);
+                        if constexpr (INNER) wr = fok && (any || (PART && v >= a.n));
                         // a row that began in an earlier group: its tail goes to the group's first slot
                         if (shared) {
                             // (the slot's address is formed here, from a value the compiler cannot
@@ -377,6 +397,7 @@ __global__ __launch_bounds__(kBlock, IFELSE ? ((COLD && VEC != 1) ? 4 : 5) : 4) 
                         for (int i = 0; i < VEC; ++i) acc[i] = 0.0f;
                         shared = false;
                         open = false;
+                        any = false;
                         ++r;
                         if (!a.row_ids) {
                             v = r;
@@ -426,6 +447,17 @@ void row_shape(int F, bool aligned16, int* vec, int* log2T) {
     *log2T = std::min(ceil_log2(frags), 6);
 }
 
+template <int VEC, int LOG2T, int U, bool INNER>
+void launch_plain(dim3 grid, dim3 block, hipStream_t s, const AggArgs& a) {
+    if (a.part) {
+        if (a.has_cold) hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, false, true, true, INNER>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, false, false, true, INNER>), grid, block, 0, s, a);
+    } else {
+        if (a.has_cold) hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, false, true, false, INNER>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, false, false, false, INNER>), grid, block, 0, s, a);
+    }
+}
+
 template <int VEC, int LOG2T, int U>
 void launch_one(hipStream_t s, const AggArgs& a) {
     const int64_t per_block = kBlock >> LOG2T;
@@ -434,14 +466,12 @@ void launch_one(hipStream_t s, const AggArgs& a) {
     const int64_t q = a.part ? a.total_rounds : (blocks_per_slice + xcds_per_slice - 1) / xcds_per_slice;
     const dim3 grid((unsigned)(q * 8)), block(kBlock);
     if (a.row_bits) {
-        if (a.has_cold) hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, true, true, false>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, true, false, false>), grid, block, 0, s, a);
-    } else if (a.part) {
-        if (a.has_cold) hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, false, true, true>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, false, false, true>), grid, block, 0, s, a);
+        if (a.has_cold) hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, true, true, false, false>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, true, false, false, false>), grid, block, 0, s, a);
+    } else if (a.zero) {
+        launch_plain<VEC, LOG2T, U, true>(grid, block, s, a);
     } else {
-        if (a.has_cold) hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, false, true, false>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((k_aggregate<VEC, LOG2T, U, false, false, false>), grid, block, 0, s, a);
+        launch_plain<VEC, LOG2T, U, false>(grid, block, s, a);
     }
 }
 
@@ -612,7 +642,12 @@ int epp_build_schedule(epp_path* p, int gs, hipStream_t s, Schedule** out) {
 }
 
 int epp_launch_aggregate(epp_path* p, Schedule* sc, int log2_slices, const float* in, float* out, int F, hipStream_t s,
-                         const unsigned int* row_bits, const unsigned int* src_bits, const Partition* part) {
+                         const unsigned int* row_bits, const unsigned int* src_bits, const Partition* part,
+                         const unsigned int* inner_rows) {
+    if (inner_rows && (row_bits || !p->has_inner || !p->zero_block.p)) {
+        epp_set_error("the path's entries are not marked for an inner path");
+        return EPP_ERR_INVALID_ARG;
+    }
     int vec, log2T;
     const bool aligned16 = ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & 15) == 0;
     row_shape(F, aligned16, &vec, &log2T);
@@ -653,6 +688,7 @@ int epp_launch_aggregate(epp_path* p, Schedule* sc, int log2_slices, const float
         for (int x = 0; x < 10; ++x) a.sec_g[x] = 0;
         a.n = 0x7FFFFFFF;
         a.part_delta = 0;
+        a.zero = inner_rows ? p->zero_block.as<float>() : nullptr;
         if (part) {
             const int per_block = kBlock >> log2T;
             int hot = 0;
@@ -676,14 +712,15 @@ int epp_launch_aggregate(epp_path* p, Schedule* sc, int log2_slices, const float
         const int64_t total = sc->n_split_rows << log2Fp;
         hipLaunchKernelGGL(k_combine_cut_rows, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
                            sc->cut_rows.as<int32_t>(), sc->n_split_rows, rowptr, row_ids, sc->gs, F,
-                           log2Fp, pieces, row_bits, out, (int)p->n, part ? part->vpart : (float*)nullptr);
+                           log2Fp, pieces, row_bits ? row_bits : inner_rows, out, (int)p->n,
+                           part ? part->vpart : (float*)nullptr);
     }
     if (part && part->n_split > 0) {
         const int log2Fp = std::min(ceil_log2(F), 6);
         const int64_t total = part->n_split << log2Fp;
         hipLaunchKernelGGL(k_combine_sections, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
                            part->mvert.as<int32_t>(), part->mptr.as<int32_t>(), part->n_split, F, log2Fp,
-                           part->vpart, out);
+                           part->vpart, inner_rows, out);
     }
     EPP_HIP_TRY(hipGetLastError());
     return EPP_OK;

@@ -22,9 +22,16 @@ Schedule* find_schedule(epp_path* p, int gs) {
     return nullptr;
 }
 
+// The path whose entry arrays, group tables and per-width choices `p` runs on: itself, or the
+// next outer path where the two share their entries.
+epp_path* entries_of(epp_path* p) { return p->outer ? p->outer : p; }
+const epp_path* entries_of(const epp_path* p) { return p->outer ? p->outer : p; }
+
 // One-off work of a (path, width): group table, partial rows, locality marks.  Allocates and
 // waits; the aggregate entry points only look the result up.
-int prepare_width(epp_path* p, int F, hipStream_t s, epp_path::WidthCfg** out) {
+int prepare_width(epp_path* self, int F, hipStream_t s, epp_path::WidthCfg** out) {
+    epp_path* p = entries_of(self);
+    self->last_F = F;
     epp_path::WidthCfg* w = width_cfg(p, F);
     if (!w->sched) {
         EPP_TRY(epp_ensure_canonical(p, s));  // (given back while all widths ran on reconstructed copies)
@@ -51,9 +58,10 @@ int check_width(int F) {
     return EPP_OK;
 }
 
-int aggregate(epp_path* p, const float* in, float* out, int F, hipStream_t s, const unsigned int* row_bits = nullptr,
+int aggregate(epp_path* self, const float* in, float* out, int F, hipStream_t s, const unsigned int* row_bits = nullptr,
               const unsigned int* src_bits = nullptr) {
-    if (!p || !in || !out) { epp_set_error("NULL argument"); return EPP_ERR_INVALID_ARG; }
+    if (!self || !in || !out) { epp_set_error("NULL argument"); return EPP_ERR_INVALID_ARG; }
+    epp_path* p = entries_of(self);
     EPP_TRY(check_width(F));
     if ((int64_t)p->n * F >= (1ll << 40)) { epp_set_error("gradient matrix too large"); return EPP_ERR_TOO_LARGE; }
     if (in == out) { epp_set_error("grad_in and grad_out must not alias"); return EPP_ERR_INVALID_ARG; }
@@ -64,10 +72,10 @@ int aggregate(epp_path* p, const float* in, float* out, int F, hipStream_t s, co
         epp_set_error("width F=%d has not been prepared on this path: call epp_path_prepare_width first", F);
         return EPP_ERR_INVALID_ARG;
     }
-    p->last_F = F;
+    self->last_F = F;
     // (the if-else baseline walks the whole graph in its given order: no partitioned layout)
     return epp_launch_aggregate(p, w->sched, w->log2_slices, in, out, F, s, row_bits, src_bits,
-                                row_bits ? nullptr : w->part);
+                                row_bits ? nullptr : w->part, self->outer ? self->inner_rows : nullptr);
 }
 
 }  // namespace
@@ -91,12 +99,16 @@ extern "C" int epp_path_info(const epp_path_t* p, epp_path_info_t* info) {
     info->max_len = p->max_len;
     for (int c = 0; c < EPP_NCLASS; ++c) info->len_hist[c] = p->len_hist[c];
     size_t bytes = p->row_ids.bytes + p->rowptr.bytes + p->cv.bytes + p->full_rowptr.bytes + p->empty_rows.bytes;
+    bytes += p->zero_block.bytes;
     for (const Schedule* s : p->scheds) bytes += s->bytes();
     for (const auto& w : p->widths)
         if (w.part) bytes += w.part->bytes();
     if (p->pool->accounted_by == p) bytes += p->pool->bytes();  // shared by the handle's paths: reported once
     info->bytes = (int64_t)bytes;
-    for (const auto& w : p->widths) {
+    info->shares_entries = p->outer ? 1 : 0;
+    // (a path that runs on the next outer path's arrays reports that path's tables as what it uses;
+    // their bytes are part of the outer path's footprint)
+    for (const auto& w : entries_of(p)->widths) {
         if (w.F == p->last_F && w.sched) {
             const Schedule* used = w.part ? w.part->sched : w.sched;
             info->sched_F = w.F;
@@ -116,7 +128,7 @@ extern "C" int epp_path_info(const epp_path_t* p, epp_path_info_t* info) {
 extern "C" int epp_select_group_size(const epp_path_t* p, int F) {
     if (!p) { epp_set_error("path is NULL"); return EPP_ERR_INVALID_ARG; }
     if (F < 1) { epp_set_error("F must be >= 1"); return EPP_ERR_INVALID_ARG; }
-    return epp_default_group_size(p, F);
+    return epp_default_group_size(entries_of(p), F);  // (groups are cut from the array the path runs on)
 }
 
 extern "C" int epp_paper_linreg_group_size(int64_t vertices, int64_t undirected_edges) {
@@ -130,9 +142,10 @@ extern "C" int epp_paper_linreg_group_size(int64_t vertices, int64_t undirected_
     return (int)(x + 0.5);
 }
 
-extern "C" int epp_path_set_group_size(epp_path_t* p, int F, int gs, epp_stream_t stream) {
-    if (!p) { epp_set_error("path is NULL"); return EPP_ERR_INVALID_ARG; }
+extern "C" int epp_path_set_group_size(epp_path_t* self, int F, int gs, epp_stream_t stream) {
+    if (!self) { epp_set_error("path is NULL"); return EPP_ERR_INVALID_ARG; }
     if (F < 1) { epp_set_error("F must be >= 1"); return EPP_ERR_INVALID_ARG; }
+    epp_path* p = entries_of(self);
     EPP_TRY(epp_ensure_canonical(p, (hipStream_t)stream));  // before the copy it would be rebuilt from goes
     EPP_HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
     epp_path::WidthCfg* w = width_cfg(p, F);
@@ -147,7 +160,7 @@ extern "C" int epp_path_set_group_size(epp_path_t* p, int F, int gs, epp_stream_
         for (const auto& x : p->widths) used |= (x.sched == p->scheds[i]);
         if (!used) { delete p->scheds[i]; p->scheds.erase(p->scheds.begin() + i); } else ++i;
     }
-    return prepare_width(p, F, (hipStream_t)stream, nullptr);
+    return prepare_width(self, F, (hipStream_t)stream, nullptr);
 }
 
 extern "C" int epp_path_prepare_width(epp_path_t* p, int F, epp_stream_t stream) {

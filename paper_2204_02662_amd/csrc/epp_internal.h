@@ -12,6 +12,14 @@
 
 #define EPP_NCLASS 32
 
+// An entry of a path is the pair (column word, weight bits).  The column word holds the source's
+// vertex id in its low 29 bits and three flags:
+constexpr int kEntRowEnd = (int)0x80000000u;  // last entry of its row
+constexpr int kEntCold = 0x40000000;           // rarely referenced source: gathered with streaming loads
+constexpr int kEntOuterOnly = 0x20000000;      // not an entry of the inner path that shares this array (below)
+constexpr int kEntCol = 0x1FFFFFFF;
+constexpr long long kMaxVertices = 0x20000000ll;  // vertex ids must leave the flag bits free
+
 void epp_set_error(const char* fmt, ...);
 
 #define EPP_HIP_TRY(expr)                                                                           \
@@ -220,7 +228,17 @@ struct epp_path {
     DevBuf store;                // one allocation behind row_ids, rowptr and cv where they are views of it
     DevBuf row_ids;              // int32[n_stream_rows] vertex of each streamed row; unset: identity
     DevBuf rowptr;               // int32[n_stream_rows + 1]
-    DevBuf cv;                   // int2[nnz]: (column id | cold flag bit 30 | row-end flag bit 31, weight bits)
+    DevBuf cv;                   // int2[nnz]: (column word, weight bits)
+    // Shared entries (Sec. 4: consecutive execution paths of a model overlap almost entirely once the
+    // active sets approach saturation).  With N^{k-1} inside N^k, every entry of the path one level
+    // further in is an entry of this one, in the same order.  Such an inner path can do without entry
+    // arrays of its own: it keeps its row ids and row pointer (canonical form, export, combination
+    // stage) and runs on this path's arrays, group tables and reconstructed copies, skipping the
+    // entries that carry kEntOuterOnly and the rows left without any entry.
+    epp_path* outer = nullptr;            // set on the inner path: the path whose entries it shares
+    const unsigned int* inner_rows = nullptr;  // set on the inner path: bitmap of its rows (owned by the handle)
+    bool has_inner = false;               // set on the outer path: kEntOuterOnly marks are in place
+    DevBuf zero_block;                    // outer path: 256 zero bytes, what a skipped entry gathers
     int cold_thr = 0;            // entries whose source is referenced fewer times than this carry the cold flag
     int cold_F = 0;              // width the cold flags were chosen for (the largest prepared width that marks)
     epp_alloc_t alloc = {nullptr, nullptr, nullptr};  // the caller's allocator (alloc == NULL: hipMalloc)
@@ -283,9 +301,10 @@ int epp_static_scratch(float** ptr);
 
 // aggregate.hip
 int epp_build_schedule(epp_path* p, int gs, hipStream_t s, Schedule** out);
+// inner_rows != NULL: the launch serves the inner path that shares p's entries (bitmap of its rows)
 int epp_launch_aggregate(epp_path* p, Schedule* sc, int log2_slices, const float* in, float* out, int F, hipStream_t s,
                          const unsigned int* row_bits = nullptr, const unsigned int* src_bits = nullptr,
-                         const Partition* part = nullptr);
+                         const Partition* part = nullptr, const unsigned int* inner_rows = nullptr);
 // group table over any (row pointer, entry count); not registered with the path
 int epp_build_schedule_over(const epp_path* p, const int32_t* rowptr, int64_t n_rows, int64_t nnz, int gs, hipStream_t s,
                             Schedule** out);

@@ -39,9 +39,7 @@
 namespace {
 
 constexpr int kBlock = 256;
-constexpr int kRowEnd = (int)0x80000000u;
-constexpr int kCold = 0x40000000;
-constexpr int kColMask = 0x3FFFFFFF;
+constexpr int kRowEnd = kEntRowEnd, kCold = kEntCold, kOuterOnly = kEntOuterOnly, kColMask = kEntCol;
 constexpr int kHot = 8;        // hot sections = XCDs
 constexpr int kSec = kHot + 1;
 constexpr int kTile = 1024;    // entries of a cut row handled by one wavefront
@@ -262,7 +260,7 @@ __global__ __launch_bounds__(kBlock) void k_part_scatter_cut(const int2v* __rest
         }
         if (sec[i] >= 0) {
             int2v e = ent[i];
-            e.x = (e.x & kColMask) | (sec[i] == kHot ? (e.x & kCold) : 0) | (last ? kRowEnd : 0);
+            e.x = (e.x & (kColMask | kOuterOnly)) | (sec[i] == kHot ? (e.x & kCold) : 0) | (last ? kRowEnd : 0);
             cv2[dest] = e;
         }
         // the section ids, two to a byte (an even lane writes its own and its neighbour's): they are

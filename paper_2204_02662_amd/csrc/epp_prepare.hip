@@ -68,7 +68,8 @@ __global__ __launch_bounds__(kBlock) void k_mark_training(const int32_t* __restr
     atomicOr(&bitmap32[v >> 5], 1u << (v & 31));
 }
 
-// keep-mask of every 64-edge segment and kept entries per tile.
+// keep-mask of every 64-edge segment and kept entries per tile; `fresh` receives the entries kept
+// at this level that the level before did not keep (all kept entries where that mask is not reused).
 //
 // `mask` may still hold the keep-mask of the previous level (have_prev).  If N^{k-1} is a
 // subset of N^k (*not_subset == 0; always the case when every vertex has a self-loop), an entry
@@ -81,8 +82,8 @@ __global__ __launch_bounds__(kBlock) void k_mark_training(const int32_t* __restr
 __global__ __launch_bounds__(kBlock) void k_edge_mask(const int32_t* __restrict__ col, int64_t nnz, int64_t n_seg,
                                                       int64_t n, const unsigned int* __restrict__ bitmap32,
                                                       int have_prev, const int* __restrict__ not_subset,
-                                                      unsigned long long* mask, int* __restrict__ tile_count,
-                                                      int* __restrict__ err) {
+                                                      unsigned long long* mask, unsigned long long* __restrict__ fresh,
+                                                      int* __restrict__ tile_count, int* __restrict__ err) {
     __shared__ int wave_cnt[4];
     const int wave = threadIdx.x >> 6, lane = lane_id();
     int cnt = 0;
@@ -92,12 +93,13 @@ __global__ __launch_bounds__(kBlock) void k_edge_mask(const int32_t* __restrict_
     const int64_t seg0 = (int64_t)blockIdx.x * kSegsPerTile + wave * kPerWave;
     const bool use_prev = have_prev && *not_subset == 0;
     bool known[kPerWave];
+    unsigned long long pm[kPerWave];
     int32_t c[kPerWave];
     unsigned int w[kPerWave];
 #pragma unroll
     for (int i = 0; i < kPerWave; ++i) {
-        const unsigned long long pm = (use_prev && seg0 + i < n_seg) ? mask[seg0 + i] : 0ull;
-        known[i] = (pm >> lane) & 1ull;
+        pm[i] = (use_prev && seg0 + i < n_seg) ? mask[seg0 + i] : 0ull;
+        known[i] = (pm[i] >> lane) & 1ull;
     }
 #pragma unroll
     for (int i = 0; i < kPerWave; ++i) {
@@ -117,7 +119,10 @@ __global__ __launch_bounds__(kBlock) void k_edge_mask(const int32_t* __restrict_
     for (int i = 0; i < kPerWave; ++i) {
         const bool keep = known[i] || (c[i] >= 0 && ((w[i] >> (c[i] & 31)) & 1u));
         const unsigned long long m = __ballot(keep);
-        if (lane == 0 && seg0 + i < n_seg) mask[seg0 + i] = m;
+        if (lane == 0 && seg0 + i < n_seg) {
+            mask[seg0 + i] = m;
+            fresh[seg0 + i] = m & ~pm[i];  // kept now, not kept at the level before
+        }
         cnt += __popcll(m);
     }
     if (lane == 0) wave_cnt[wave] = cnt;
@@ -198,25 +203,30 @@ __global__ __launch_bounds__(64) void k_seg_base(const unsigned long long* __res
 }
 
 // Stable compaction of the kept entries into interleaved (col, val) pairs: a kept entry of
-// segment s goes to seg_base[s] + (kept entries before it in the segment).
+// segment s goes to seg_base[s] + (kept entries before it in the segment).  With `fresh` (the
+// entries that the level before did not keep) those entries get the kEntOuterOnly mark: the
+// path of the level before will run on this array.
 __global__ __launch_bounds__(kBlock) void k_edge_extract(const int32_t* __restrict__ col, const float* __restrict__ val,
                                                          int64_t n_seg, const unsigned long long* __restrict__ mask,
+                                                         const unsigned long long* __restrict__ fresh,
                                                          const int* __restrict__ seg_base, int2* __restrict__ cv) {
     const int wave = threadIdx.x >> 6, lane = lane_id();
     constexpr int kPerWave = kSegsPerTile / 4;
-    unsigned long long m[kPerWave];
+    unsigned long long m[kPerWave], fr[kPerWave];
     int sb[kPerWave];
     int2 x[kPerWave];
 #pragma unroll
     for (int i = 0; i < kPerWave; ++i) {
         const int64_t seg = (int64_t)blockIdx.x * kSegsPerTile + wave * kPerWave + i;
         m[i] = seg < n_seg ? mask[seg] : 0ull;
+        fr[i] = (fresh && seg < n_seg) ? fresh[seg] : 0ull;
         sb[i] = seg < n_seg ? seg_base[seg] : 0;
     }
 #pragma unroll
     for (int i = 0; i < kPerWave; ++i) {
         const int64_t e = ((int64_t)blockIdx.x * kSegsPerTile + wave * kPerWave + i) * 64 + lane;
-        if ((m[i] >> lane) & 1ull) x[i] = make_int2(col[e], __float_as_int(val[e]));
+        if ((m[i] >> lane) & 1ull)
+            x[i] = make_int2(col[e] | (((fr[i] >> lane) & 1ull) ? kEntOuterOnly : 0), __float_as_int(val[e]));
     }
 #pragma unroll
     for (int i = 0; i < kPerWave; ++i) {
@@ -356,8 +366,43 @@ __global__ __launch_bounds__(kBlock) void k_deinterleave(const int2* __restrict_
     int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (e < nnz) {
         int2 x = cv[e];
-        if (col) col[e] = x.x & 0x3FFFFFFF;  // bits 30 and 31 are the cold and row-end flags
+        if (col) col[e] = x.x & kEntCol;  // (the high bits are flags)
         if (val) val[e] = __int_as_float(x.y);
+    }
+}
+
+// Entries of an inner path that shares the arrays of `outer` (canonical form, for export): row r of
+// the inner path is the row of the same vertex in the outer path without the entries that carry
+// the kEntOuterOnly mark, in the same order.  One wavefront per inner row.
+__global__ __launch_bounds__(kBlock) void k_export_inner(const int32_t* __restrict__ row_ids,
+                                                         const int32_t* __restrict__ rowptr, int64_t n_rows,
+                                                         const int32_t* __restrict__ o_row_ids,
+                                                         const int32_t* __restrict__ o_rowptr, int64_t o_rows,
+                                                         const int2* __restrict__ o_cv, int32_t* __restrict__ col,
+                                                         float* __restrict__ val) {
+    const int64_t r = (int64_t)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
+    if (r >= n_rows) return;
+    const int lane = lane_id();
+    const int32_t v = row_ids[r];
+    int64_t lo = 0, hi = o_rows - 1;  // the outer row of vertex v (it exists: the inner rows are outer rows)
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (o_row_ids[mid] < v) lo = mid + 1; else hi = mid;
+    }
+    int dst = rowptr[r];
+    const int dst_end = rowptr[r + 1];
+    for (int j0 = o_rowptr[lo]; j0 < o_rowptr[lo + 1]; j0 += 64) {
+        const int j = j0 + lane;
+        const bool in_row = j < o_rowptr[lo + 1];
+        const int2 x = in_row ? o_cv[j] : make_int2(kEntOuterOnly, 0);
+        const bool keep = !(x.x & kEntOuterOnly);
+        const unsigned long long m = __ballot(keep);
+        const int at = dst + __popcll(m & low_mask(lane));
+        if (keep && at < dst_end) {  // (the bound only guards against arrays that do not belong together)
+            if (col) col[at] = x.x & kEntCol;
+            if (val) val[at] = __int_as_float(x.y);
+        }
+        dst += __popcll(m);
     }
 }
 
@@ -435,8 +480,8 @@ struct HostScalars {
 int validate_csr(const epp_csr_t* g) {
     if (!g) { epp_set_error("graph is NULL"); return EPP_ERR_INVALID_ARG; }
     if (g->n < 0 || g->nnz < 0) { epp_set_error("negative graph size"); return EPP_ERR_INVALID_ARG; }
-    if (g->n >= 0x40000000ll || g->nnz >= 0x7FFFFFFFll) {
-        epp_set_error("graph too large: n=%lld (limit 2^30-1) nnz=%lld (limit 2^31-1)", (long long)g->n,
+    if (g->n >= kMaxVertices || g->nnz >= 0x7FFFFFFFll) {
+        epp_set_error("graph too large: n=%lld (limit 2^29-1) nnz=%lld (limit 2^31-1)", (long long)g->n,
                       (long long)g->nnz);
         return EPP_ERR_TOO_LARGE;
     }
@@ -501,6 +546,11 @@ __global__ __launch_bounds__(kBlock) void k_check_cols(const int32_t* __restrict
 }
 
 // Message and code for the error bits raised by the input checks (bit 0 row pointer, bit 1 ids).
+long long env_share_pct() {
+    const char* e = std::getenv("EPP_TUNE_SHARE_PCT");
+    return (e && *e) ? std::atoll(e) : 95;
+}
+
 int input_error(int bits, int64_t n) {
     if (bits & 2) { epp_set_error("a column id lies outside [0, %lld)", (long long)n); return EPP_ERR_OUT_OF_RANGE_ID; }
     epp_set_error("the row pointer does not rise from 0 to nnz");
@@ -595,23 +645,24 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
     }
 
     // all temporaries of the construction come from one allocation
-    DevBuf mask, seg_base, tile_cnt, tile_base, scan_tmp, newptr, dev_total, err, not_subset, stats;
+    DevBuf mask, fresh, seg_base, tile_cnt, tile_base, scan_tmp, newptr, dev_total, err, stats;
     const size_t max_tiles = std::max<size_t>(std::max(edge_tiles, word_tiles), 1);
     const size_t stats_bytes = kStatWords * sizeof(unsigned long long);
     DevArena arena;
-    EPP_TRY(arena.reserve(DevArena::rounded((size_t)n_seg * 8) + DevArena::rounded((size_t)n_seg * 4) +
+    EPP_TRY(arena.reserve(2 * DevArena::rounded((size_t)n_seg * 8) + DevArena::rounded((size_t)n_seg * 4) +
                           2 * DevArena::rounded(max_tiles * 4) + DevArena::rounded(scan_tmp_bytes(edge_tiles)) +
                           DevArena::rounded((size_t)(n + 1) * 4) +
-                          3 * DevArena::rounded(32) + DevArena::rounded(stats_bytes), al));
+                          2 * DevArena::rounded(32) + DevArena::rounded(stats_bytes), al));
     arena.take(&mask, (size_t)n_seg * 8);
+    arena.take(&fresh, (size_t)n_seg * 8);
     arena.take(&seg_base, (size_t)n_seg * 4);
     arena.take(&tile_cnt, max_tiles * 4);
     arena.take(&tile_base, max_tiles * 4);
     arena.take(&scan_tmp, scan_tmp_bytes(edge_tiles));
     arena.take(&newptr, (size_t)(n + 1) * 4);
-    arena.take(&dev_total, 3 * sizeof(long long));  // [0] kept entries, [1] rows of the level, [2] input error bits
+    // [0] kept entries, [1] rows of the level, [2] input error bits, [3] "N^{k-1} is not inside N^k"
+    arena.take(&dev_total, 4 * sizeof(long long));
     arena.take(&err, sizeof(int));
-    arena.take(&not_subset, sizeof(int));
     arena.take(&stats, stats_bytes);
     EPP_HIP_TRY(hipMemsetAsync(err.p, 0, sizeof(int), s));
     EPP_HIP_TRY(hipMemsetAsync(newptr.p, 0, newptr.bytes, s));
@@ -649,18 +700,18 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
         p->n_src = P->set_size[k];
         long long* d_total = dev_total.as<long long>();
         int* d_err = reinterpret_cast<int*>(d_total + 2);
-        EPP_HIP_TRY(hipMemsetAsync(d_total, 0, 3 * sizeof(long long), s));
+        int* d_not_subset = reinterpret_cast<int*>(d_total + 3);
+        EPP_HIP_TRY(hipMemsetAsync(d_total, 0, 4 * sizeof(long long), s));
         if (edge_tiles) {
             // from the second level on the mask of the level before is reused where N^{k-1} lies in N^k
             if (k > 0) {
-                EPP_HIP_TRY(hipMemsetAsync(not_subset.p, 0, sizeof(int), s));
                 hipLaunchKernelGGL(k_bitmap_not_subset, dim3(grid_for(n_words, kBlock)), dim3(kBlock), 0, s,
                                    P->bitmaps[k - 1].as<unsigned long long>(), P->bitmaps[k].as<unsigned long long>(),
-                                   n_words, not_subset.as<int>());
+                                   n_words, d_not_subset);
             }
             hipLaunchKernelGGL(k_edge_mask, dim3(edge_tiles), dim3(kBlock), 0, s, g->col, nnz, n_seg, n,
-                               P->bitmaps[k].as<unsigned int>(), k > 0 ? 1 : 0, not_subset.as<int>(),
-                               mask.as<unsigned long long>(), tile_cnt.as<int>(), d_err);
+                               P->bitmaps[k].as<unsigned int>(), k > 0 ? 1 : 0, (const int*)d_not_subset,
+                               mask.as<unsigned long long>(), fresh.as<unsigned long long>(), tile_cnt.as<int>(), d_err);
             scan_counts(tile_cnt.as<int>(), tile_base.as<int>(), (int64_t)edge_tiles, d_total, scan_tmp.as<int>(), s);
             hipLaunchKernelGGL(k_seg_base, dim3(edge_tiles), dim3(64), 0, s, mask.as<unsigned long long>(), n_seg,
                                tile_base.as<int>(), seg_base.as<int>());
@@ -678,7 +729,7 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
                                (int64_t)word_tiles, d_total + 1);
             EPP_HIP_TRY(hipGetLastError());
         }
-        EPP_HIP_TRY(hipMemcpyAsync(hs.p, d_total, 3 * sizeof(long long), hipMemcpyDeviceToHost, s));
+        EPP_HIP_TRY(hipMemcpyAsync(hs.p, d_total, 4 * sizeof(long long), hipMemcpyDeviceToHost, s));
         EPP_HIP_TRY(hipStreamSynchronize(s));
         if (hs.p[2] != 0) return input_error((int)hs.p[2], n);
         if (n == 0 && nnz > 0) return input_error(2, n);
@@ -695,9 +746,28 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
         char* base = p->store.as<char>();
         p->row_ids.view(base, ids_bytes);
         p->rowptr.view(base + DevArena::rounded(ids_bytes), ptr_bytes);
+        // Shared entries: the path of the level before runs on this path's arrays if nearly all of
+        // this path's entries are its own too (the extra entries are skipped one by one at run time,
+        // so the inner layer pays for them; EPP_TUNE_SHARE_PCT, default 95, 0: never).  Every other
+        // level at most: a path whose marks serve an inner path keeps its own arrays.
+        epp_path* inner = nullptr;
+        if (k > 0 && kept > 0 && (int)hs.p[3] == 0) {
+            epp_path* q = built[k - 1];
+            const long long pct = env_share_pct();
+            if (pct > 0 && !q->has_inner && !q->outer && q->nnz > 0 && q->nnz * 100 >= kept * pct) inner = q;
+        }
         if (edge_tiles) {
             hipLaunchKernelGGL(k_edge_extract, dim3(edge_tiles), dim3(kBlock), 0, s, g->col, g->val, n_seg,
-                               mask.as<unsigned long long>(), seg_base.as<int>(), p->cv.as<int2>());
+                               mask.as<unsigned long long>(), inner ? fresh.as<unsigned long long>() : nullptr,
+                               seg_base.as<int>(), p->cv.as<int2>());
+        }
+        if (inner) {
+            EPP_TRY(p->zero_block.alloc(256, al));
+            EPP_HIP_TRY(hipMemsetAsync(p->zero_block.p, 0, 256, s));
+            p->has_inner = true;
+            inner->outer = p;
+            inner->inner_rows = P->bitmaps[k].as<unsigned int>();  // its rows are N^k
+            inner->cv.release();  // (stream-ordered: whoever gets the block next uses it on this stream or later)
         }
         if (n > 0) {
             hipLaunchKernelGGL(k_bitmap_compact, dim3(word_tiles), dim3(kBlock), 0, s,
@@ -822,7 +892,7 @@ extern "C" int epp_paths_import(int64_t n, int L, const int32_t* train_ids, int6
     *out = nullptr;
     if (L < 1 || !layers) { epp_set_error("L must be >= 1 and layers non-NULL"); return EPP_ERR_INVALID_ARG; }
     if (n < 0 || n_train < 0 || (n_train > 0 && !train_ids)) { epp_set_error("bad sizes"); return EPP_ERR_INVALID_ARG; }
-    if (n >= 0x40000000ll) { epp_set_error("graph too large: n=%lld (limit 2^30-1)", (long long)n); return EPP_ERR_TOO_LARGE; }
+    if (n >= kMaxVertices) { epp_set_error("graph too large: n=%lld (limit 2^29-1)", (long long)n); return EPP_ERR_TOO_LARGE; }
     for (int l = 0; l < L; ++l) {
         const epp_path_arrays_t& a = layers[l];
         if (a.n_rows < 0 || a.n_rows > n || a.nnz < 0 || !a.rowptr || (a.n_rows > 0 && !a.row_ids) ||
@@ -937,12 +1007,22 @@ extern "C" int epp_path_export(const epp_path_t* p, int32_t* row_ids, int32_t* r
         EPP_HIP_TRY(hipMemcpyAsync(rowptr, ptr, (size_t)(p->n_rows + 1) * 4, hipMemcpyDeviceToDevice, s));
     }
     if ((col || val) && p->nnz > 0) {
-        EPP_TRY(epp_ensure_canonical(const_cast<epp_path*>(p), s));
-        hipLaunchKernelGGL(k_deinterleave, dim3(grid_for(p->nnz, kBlock)), dim3(kBlock), 0, s, p->cv.as<int2>(), p->nnz,
-                           col, val);
+        if (p->outer) {  // the entries live in the outer path's array
+            epp_path* o = p->outer;
+            EPP_TRY(epp_ensure_canonical(o, s));
+            hipLaunchKernelGGL(k_export_inner, dim3(grid_for(p->n_rows, kBlock / 64)), dim3(kBlock), 0, s,
+                               p->row_ids.as<int32_t>(), p->rowptr.as<int32_t>(), p->n_rows, o->row_ids.as<int32_t>(),
+                               o->rowptr.as<int32_t>(), o->n_stream_rows, o->cv.as<int2>(), col, val);
+        } else {
+            EPP_TRY(epp_ensure_canonical(const_cast<epp_path*>(p), s));
+            hipLaunchKernelGGL(k_deinterleave, dim3(grid_for(p->nnz, kBlock)), dim3(kBlock), 0, s, p->cv.as<int2>(),
+                               p->nnz, col, val);
+        }
     }
     EPP_HIP_TRY(hipGetLastError());
     EPP_HIP_TRY(hipStreamSynchronize(s));
+    // (an entry array that was rebuilt for this call only is given back again)
+    epp_release_canonical_if_unused(p->outer ? p->outer : const_cast<epp_path*>(p));
     return EPP_OK;
 }
 

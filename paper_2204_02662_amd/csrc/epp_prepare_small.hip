@@ -27,7 +27,7 @@ constexpr int kMaxEntries = 2 * kMaxItems;
 constexpr int kEntryWords = kMaxEntries / 64;  // = 2 * kThreads: two keep-mask words per thread
 constexpr int kStatWords = EPP_NCLASS + 1; // histogram + longest row
 constexpr int kLevelWords = 3 + kStatWords; // kept entries, rows, "set did not change", statistics
-constexpr int kRowEnd = (int)0x80000000u;
+constexpr int kRowEnd = kEntRowEnd;
 constexpr int kBatch = 8;                  // independent loads in flight per lane in the streaming loops
 
 __device__ __forceinline__ unsigned long long low_mask(int lane) { return (1ull << lane) - 1ull; }

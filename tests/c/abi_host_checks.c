@@ -32,7 +32,7 @@ int main(void) {
     g.val = &fdummy;
     CHECK(epp_prepare(&g, NULL, 0, 0, NULL, NULL, &paths) == EPP_ERR_INVALID_ARG);  /* L < 1 */
     CHECK(epp_prepare(&g, NULL, 3, 2, NULL, NULL, &paths) == EPP_ERR_INVALID_ARG);  /* ids NULL */
-    g.n = (int64_t)1 << 30;
+    g.n = (int64_t)1 << 29;
     CHECK(epp_prepare(&g, NULL, 0, 2, &no_alloc, NULL, &paths) == EPP_ERR_TOO_LARGE);
     CHECK(epp_prepare_full(&g, &no_alloc, NULL, &full) == EPP_ERR_TOO_LARGE);
     g.n = -1;

@@ -42,7 +42,7 @@ def test_host_side_argument_checks_need_no_gpu():
     assert lib.epp_path_prepare_width(None, 16, None) == epp.EPP_ERR_INVALID_ARG
     # size limits are checked before anything is dereferenced or sent to the GPU
     dummy = ctypes.c_void_p(16)
-    for n, nnz, want in ((1 << 30, 10, epp.EPP_ERR_TOO_LARGE), (10, (1 << 31) - 1, epp.EPP_ERR_TOO_LARGE),
+    for n, nnz, want in ((1 << 29, 10, epp.EPP_ERR_TOO_LARGE), (10, (1 << 31) - 1, epp.EPP_ERR_TOO_LARGE),
                          (-1, 0, epp.EPP_ERR_INVALID_ARG)):
         csr = epp._Csr(n, nnz, dummy, dummy, dummy)
         assert lib.epp_prepare(ctypes.byref(csr), None, 0, 2, None, None, ctypes.byref(out)) == want

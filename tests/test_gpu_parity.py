@@ -426,6 +426,60 @@ def test_canonical_entries_are_given_back_and_rebuilt(monkeypatch):
         assert_paths_bit_exact(paths, sets_o, paths_o, 2)
 
 
+@pytest.mark.parametrize("L", [2, 3])
+@pytest.mark.parametrize("layout", ["plain", "partitioned", "cold"])
+def test_inner_path_runs_on_the_entries_of_the_next_outer_path(monkeypatch, L, layout):
+    """With nested active sets the path of layer l is a sub-sequence of the path of layer l - 1.
+    Forced on at any overlap (EPP_TUNE_SHARE_PCT=1), the inner path keeps no entry arrays and
+    runs on the outer path's: here it holds a minority of the outer path's entries and rows, so most
+    entries are skipped and most rows must stay untouched.  Every row of every layer against the
+    oracle at lane widths of 4, 8 and 16 bytes, with small groups that cut many rows, sources
+    outside the layer's source set poisoned (the outer path's extra entries must not be read),
+    rows outside the layer's row set untouched, bit-identical repeats, the exported canonical
+    form bit-exact, and the memory the sharing saves."""
+    g = graphgen.random_graph("rmat", 30_000, seed=371, raw_draws=400_000)
+    train = graphgen.training_set(g.n, 1500, 372)
+    sets_o, paths_o = oprep(g, train, L)
+    if layout == "partitioned":
+        monkeypatch.setenv("EPP_TUNE_PART", "2")
+        monkeypatch.setenv("EPP_TUNE_PART_KB", "64")
+        monkeypatch.setenv("EPP_TUNE_PART_MINLEN", "8")
+    if layout == "cold":
+        monkeypatch.setenv("EPP_TUNE_HOT_MB", "1")
+    held = {}
+    for pct in ("0", "1"):
+        monkeypatch.setenv("EPP_TUNE_SHARE_PCT", pct)
+        paths = gpu_prepare(g, train, L)
+        shares = [paths.path(l).info().shares_entries for l in range(L)]
+        # the innermost path shares with the next one; a path whose marks serve an inner path keeps its arrays
+        assert shares == ([0] * L if pct == "0" else [0] * (L - 2) + [0, 1]), shares
+        for l in range(L):
+            src, rows = sets_o[L - l - 1], sets_o[L - l].astype(bool)
+            p = paths.path(l)
+            for F in (128, 41, 6) if layout != "cold" else (128, 130):
+                X = graphgen.normal_rows(g.n, F, src, 373 + l)
+                want = oracle.path_aggregate(g.n, paths_o[l], X)
+                for gs in (0, 24):
+                    p.set_group_size(F, gs)
+                    got = run_partial(p, X, poison=9.0)
+                    assert np.all(got[~rows] == 9.0), f"share {pct} {layout} l={l} F={F} gs={gs}: row outside the path written"
+                    assert_close(got[rows], want[rows], f"share {pct} {layout} l={l} F={F} gs={gs}")
+                    again = run_partial(p, X, poison=float("nan"))
+                    assert np.array_equal(got[rows], again[rows])
+                    Xp = X.copy()
+                    Xp[src == 0] = np.nan
+                    assert_close(run_partial(p, Xp), want, f"share {pct} {layout} l={l} F={F} gs={gs}, nan-poison")
+                i = p.info()
+                if layout == "partitioned":
+                    assert i.part_rows > 0
+                if pct == "1" and shares[l]:
+                    assert i.n_groups >= -(-paths_o[l - 1].col.size // 24)  # groups of the outer path's entries
+        assert_paths_bit_exact(paths, sets_o, paths_o, L)
+        held[pct] = sum(paths.path(l).info().bytes for l in range(L))
+    # the shared path holds row ids and row pointer only
+    assert held["1"] <= held["0"] - 8 * paths_o[L - 1].col.size + (1 << 16), held
+
+
 def test_marks_of_a_path_do_not_depend_on_the_order_of_its_widths(monkeypatch):
     """One path used at two widths: the streamed-source marks are those of the wider width,
     whichever was prepared first, and results stay within tolerance either way."""
