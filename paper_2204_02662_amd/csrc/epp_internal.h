@@ -284,7 +284,9 @@ struct epp_paths {
 // histogram + max length of a built path; `stats_scratch`: (EPP_NCLASS + 1) * 8 device bytes, or NULL
 // `host_later` (pinned host memory, EPP_NCLASS + 1 words): the statistics are copied there
 // without waiting; the caller hands them to epp_path_set_stats after it has synchronised
-int epp_path_finish(epp_path* p, hipStream_t s, void* stats_scratch = nullptr, unsigned long long* host_later = nullptr);
+// mark_row_ends = false: the entry array is not there yet (the caller marks the row ends itself)
+int epp_path_finish(epp_path* p, hipStream_t s, void* stats_scratch = nullptr, unsigned long long* host_later = nullptr,
+                    bool mark_row_ends = true);
 void epp_path_set_stats(epp_path* p, const unsigned long long* host);
 // ascending vertex ids of N^k (device, owned by `p`); allocates nothing, never waits
 int epp_active_ids(const epp_paths* p, int k, const int32_t** ids, int64_t* count);

@@ -68,10 +68,9 @@ __global__ __launch_bounds__(kBlock) void k_mark_training(const int32_t* __restr
     atomicOr(&bitmap32[v >> 5], 1u << (v & 31));
 }
 
-// keep-mask of every 64-edge segment and kept entries per tile; `fresh` receives the entries kept
-// at this level that the level before did not keep (all kept entries where that mask is not reused).
+// keep-mask of every 64-edge segment and kept entries per tile.
 //
-// `mask` may still hold the keep-mask of the previous level (have_prev).  If N^{k-1} is a
+// `prev` is the keep-mask of the previous level, or NULL.  If N^{k-1} is a
 // subset of N^k (*not_subset == 0; always the case when every vertex has a self-loop), an entry
 // kept at the previous level has its column in N^{k-1}, hence in N^k, and is kept again: only
 // the other entries are loaded and looked up.  Once the sets are close to saturation this
@@ -81,8 +80,9 @@ __global__ __launch_bounds__(kBlock) void k_mark_training(const int32_t* __restr
 // [0, n) raises bit 1 of *err and is treated as not kept, so it is never used as an index.
 __global__ __launch_bounds__(kBlock) void k_edge_mask(const int32_t* __restrict__ col, int64_t nnz, int64_t n_seg,
                                                       int64_t n, const unsigned int* __restrict__ bitmap32,
-                                                      int have_prev, const int* __restrict__ not_subset,
-                                                      unsigned long long* mask, unsigned long long* __restrict__ fresh,
+                                                      const unsigned long long* __restrict__ prev,
+                                                      const int* __restrict__ not_subset,
+                                                      unsigned long long* __restrict__ mask,
                                                       int* __restrict__ tile_count, int* __restrict__ err) {
     __shared__ int wave_cnt[4];
     const int wave = threadIdx.x >> 6, lane = lane_id();
@@ -91,15 +91,14 @@ __global__ __launch_bounds__(kBlock) void k_edge_mask(const int32_t* __restrict_
     // issued back to back so that the two dependent memory latencies are paid once per tile
     constexpr int kPerWave = kSegsPerTile / 4;
     const int64_t seg0 = (int64_t)blockIdx.x * kSegsPerTile + wave * kPerWave;
-    const bool use_prev = have_prev && *not_subset == 0;
+    const bool use_prev = prev && *not_subset == 0;
     bool known[kPerWave];
-    unsigned long long pm[kPerWave];
     int32_t c[kPerWave];
     unsigned int w[kPerWave];
 #pragma unroll
     for (int i = 0; i < kPerWave; ++i) {
-        pm[i] = (use_prev && seg0 + i < n_seg) ? mask[seg0 + i] : 0ull;
-        known[i] = (pm[i] >> lane) & 1ull;
+        const unsigned long long pm = (use_prev && seg0 + i < n_seg) ? prev[seg0 + i] : 0ull;
+        known[i] = (pm >> lane) & 1ull;
     }
 #pragma unroll
     for (int i = 0; i < kPerWave; ++i) {
@@ -119,10 +118,7 @@ __global__ __launch_bounds__(kBlock) void k_edge_mask(const int32_t* __restrict_
     for (int i = 0; i < kPerWave; ++i) {
         const bool keep = known[i] || (c[i] >= 0 && ((w[i] >> (c[i] & 31)) & 1u));
         const unsigned long long m = __ballot(keep);
-        if (lane == 0 && seg0 + i < n_seg) {
-            mask[seg0 + i] = m;
-            fresh[seg0 + i] = m & ~pm[i];  // kept now, not kept at the level before
-        }
+        if (lane == 0 && seg0 + i < n_seg) mask[seg0 + i] = m;
         cnt += __popcll(m);
     }
     if (lane == 0) wave_cnt[wave] = cnt;
@@ -203,12 +199,12 @@ __global__ __launch_bounds__(64) void k_seg_base(const unsigned long long* __res
 }
 
 // Stable compaction of the kept entries into interleaved (col, val) pairs: a kept entry of
-// segment s goes to seg_base[s] + (kept entries before it in the segment).  With `fresh` (the
-// entries that the level before did not keep) those entries get the kEntOuterOnly mark: the
-// path of the level before will run on this array.
+// segment s goes to seg_base[s] + (kept entries before it in the segment).  With `inner` (the
+// keep-mask of the level before, a subset of `mask`) the entries that level did not keep get
+// the kEntOuterOnly mark: the path of the level before will run on this array.
 __global__ __launch_bounds__(kBlock) void k_edge_extract(const int32_t* __restrict__ col, const float* __restrict__ val,
                                                          int64_t n_seg, const unsigned long long* __restrict__ mask,
-                                                         const unsigned long long* __restrict__ fresh,
+                                                         const unsigned long long* __restrict__ inner,
                                                          const int* __restrict__ seg_base, int2* __restrict__ cv) {
     const int wave = threadIdx.x >> 6, lane = lane_id();
     constexpr int kPerWave = kSegsPerTile / 4;
@@ -219,7 +215,7 @@ __global__ __launch_bounds__(kBlock) void k_edge_extract(const int32_t* __restri
     for (int i = 0; i < kPerWave; ++i) {
         const int64_t seg = (int64_t)blockIdx.x * kSegsPerTile + wave * kPerWave + i;
         m[i] = seg < n_seg ? mask[seg] : 0ull;
-        fr[i] = (fresh && seg < n_seg) ? fresh[seg] : 0ull;
+        fr[i] = (inner && seg < n_seg) ? (m[i] & ~inner[seg]) : 0ull;
         sb[i] = seg < n_seg ? seg_base[seg] : 0;
     }
 #pragma unroll
@@ -571,7 +567,8 @@ void epp_path_set_stats(epp_path* p, const unsigned long long* host) {
     p->max_len = mx;
 }
 
-int epp_path_finish(epp_path* p, hipStream_t s, void* stats_scratch, unsigned long long* host_later) {
+int epp_path_finish(epp_path* p, hipStream_t s, void* stats_scratch, unsigned long long* host_later,
+                    bool mark_row_ends) {
     DevBuf stats;
     if (stats_scratch) stats.view(stats_scratch, (EPP_NCLASS + 1) * sizeof(unsigned long long));
     else EPP_TRY(stats.alloc((EPP_NCLASS + 1) * sizeof(unsigned long long), epp_alloc_of(p)));
@@ -594,7 +591,7 @@ int epp_path_finish(epp_path* p, hipStream_t s, void* stats_scratch, unsigned lo
         EPP_HIP_TRY(hipStreamSynchronize(s));
         epp_path_set_stats(p, host);
     }
-    if (p->n_stream_rows > 0) {
+    if (mark_row_ends && p->n_stream_rows > 0) {
         hipLaunchKernelGGL(k_mark_row_ends, dim3(grid_for(p->n_stream_rows, kBlock)), dim3(kBlock), 0, s,
                            p->rowptr.as<int32_t>(), p->n_stream_rows, p->cv.as<int2>());
         EPP_HIP_TRY(hipGetLastError());
@@ -645,17 +642,20 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
     }
 
     // all temporaries of the construction come from one allocation
-    DevBuf mask, fresh, seg_base, tile_cnt, tile_base, scan_tmp, newptr, dev_total, err, stats;
+    // (keep-mask and segment offsets twice: the entries of a level are extracted once the next
+    // level has shown whether the two paths share them, so two levels' masks are alive at a time)
+    DevBuf mask[2], seg_base[2], tile_cnt, tile_base, scan_tmp, newptr, dev_total, err, stats;
     const size_t max_tiles = std::max<size_t>(std::max(edge_tiles, word_tiles), 1);
     const size_t stats_bytes = kStatWords * sizeof(unsigned long long);
     DevArena arena;
-    EPP_TRY(arena.reserve(2 * DevArena::rounded((size_t)n_seg * 8) + DevArena::rounded((size_t)n_seg * 4) +
+    EPP_TRY(arena.reserve(2 * DevArena::rounded((size_t)n_seg * 8) + 2 * DevArena::rounded((size_t)n_seg * 4) +
                           2 * DevArena::rounded(max_tiles * 4) + DevArena::rounded(scan_tmp_bytes(edge_tiles)) +
                           DevArena::rounded((size_t)(n + 1) * 4) +
                           2 * DevArena::rounded(32) + DevArena::rounded(stats_bytes), al));
-    arena.take(&mask, (size_t)n_seg * 8);
-    arena.take(&fresh, (size_t)n_seg * 8);
-    arena.take(&seg_base, (size_t)n_seg * 4);
+    for (int i = 0; i < 2; ++i) {
+        arena.take(&mask[i], (size_t)n_seg * 8);
+        arena.take(&seg_base[i], (size_t)n_seg * 4);
+    }
     arena.take(&tile_cnt, max_tiles * 4);
     arena.take(&tile_base, max_tiles * 4);
     arena.take(&scan_tmp, scan_tmp_bytes(edge_tiles));
@@ -685,12 +685,38 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
                            dev_total, hs, al, s));
 
     // One level: everything that only needs the two counts (kept entries, rows) on the device is
-    // enqueued first, the host waits once for both, makes one allocation for the path's three
-    // arrays, and enqueues the passes that fill them.  The row-length statistics come back
-    // through pinned memory and are read after the last level.
+    // enqueued first, the host waits once for both, allocates the level's arrays, and enqueues
+    // the passes that fill them.  The row-length statistics come back through pinned memory and
+    // are read after the last level.
+    //
+    // Shared entries: the path of a level runs on the arrays of the next level's path if nearly
+    // all of that path's entries are its own too (the extra entries are skipped one by one at
+    // run time, so the inner layer pays for them; EPP_TUNE_SHARE_PCT, default 95, 0: never).
+    // A level's entries are therefore extracted only when the next level's count is known: not
+    // at all if it shares them, and the outer path's extraction marks the entries that are not
+    // the inner path's.  Every other level at most: a path whose marks serve an inner path
+    // keeps its own arrays.
     std::vector<epp_path*> built;  // in level order, for the statistics
+    struct { epp_path* p = nullptr; int slot = 0; } pending;  // path whose entries are not extracted yet
+    auto extract = [&](epp_path* q, int slot, const unsigned long long* inner_mask) -> int {
+        // the entries in an allocation of their own (it can be given back once every prepared width
+        // runs on a reconstructed copy)
+        EPP_TRY(q->cv.alloc((size_t)q->nnz * sizeof(int2), al));
+        if (edge_tiles) {
+            hipLaunchKernelGGL(k_edge_extract, dim3(edge_tiles), dim3(kBlock), 0, s, g->col, g->val, n_seg,
+                               mask[slot].as<unsigned long long>(), inner_mask, seg_base[slot].as<int>(), q->cv.as<int2>());
+        }
+        if (q->n_stream_rows > 0) {
+            hipLaunchKernelGGL(k_mark_row_ends, dim3(grid_for(q->n_stream_rows, kBlock)), dim3(kBlock), 0, s,
+                               q->rowptr.as<int32_t>(), q->n_stream_rows, q->cv.as<int2>());
+        }
+        EPP_HIP_TRY(hipGetLastError());
+        return EPP_OK;
+    };
+    const long long share_pct = env_share_pct();
     for (int k = 0; k < L; ++k) {
         const int l = L - 1 - k;  // rows N^{k+1} = N^{L-l}, sources N^k = N^{L-l-1}
+        const int slot = k & 1;
         epp_path* p = new epp_path();
         P->path[l] = p;
         built.push_back(p);
@@ -710,16 +736,17 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
                                    n_words, d_not_subset);
             }
             hipLaunchKernelGGL(k_edge_mask, dim3(edge_tiles), dim3(kBlock), 0, s, g->col, nnz, n_seg, n,
-                               P->bitmaps[k].as<unsigned int>(), k > 0 ? 1 : 0, (const int*)d_not_subset,
-                               mask.as<unsigned long long>(), fresh.as<unsigned long long>(), tile_cnt.as<int>(), d_err);
+                               P->bitmaps[k].as<unsigned int>(),
+                               k > 0 ? mask[slot ^ 1].as<unsigned long long>() : (const unsigned long long*)nullptr,
+                               (const int*)d_not_subset, mask[slot].as<unsigned long long>(), tile_cnt.as<int>(), d_err);
             scan_counts(tile_cnt.as<int>(), tile_base.as<int>(), (int64_t)edge_tiles, d_total, scan_tmp.as<int>(), s);
-            hipLaunchKernelGGL(k_seg_base, dim3(edge_tiles), dim3(64), 0, s, mask.as<unsigned long long>(), n_seg,
-                               tile_base.as<int>(), seg_base.as<int>());
+            hipLaunchKernelGGL(k_seg_base, dim3(edge_tiles), dim3(64), 0, s, mask[slot].as<unsigned long long>(), n_seg,
+                               tile_base.as<int>(), seg_base[slot].as<int>());
             EPP_HIP_TRY(hipGetLastError());
         }
         if (n > 0) {
             hipLaunchKernelGGL(k_row_flags, dim3(grid_for(n, kBlock)), dim3(kBlock), 0, s, g->rowptr, n, nnz,
-                               mask.as<unsigned long long>(), seg_base.as<int>(), (const long long*)d_total,
+                               mask[slot].as<unsigned long long>(), seg_base[slot].as<int>(), (const long long*)d_total,
                                newptr.as<int>(), P->bitmaps[k + 1].as<unsigned long long>(), d_err);
             // rows of the level: set bits of the new bitmap, counted per tile of words and scanned
             // (the edge-tile offsets are no longer needed: seg_base holds them)
@@ -734,41 +761,17 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
         if (hs.p[2] != 0) return input_error((int)hs.p[2], n);
         if (n == 0 && nnz > 0) return input_error(2, n);
         const long long kept = hs.p[0], R = hs.p[1];
+        const bool nested = (int)hs.p[3] == 0;
         p->nnz = kept;
         p->n_rows = R;
         p->n_stream_rows = R;  // every row of a path has at least one entry
         P->set_size[k + 1] = R;
-        // the entries in an allocation of their own (it can be given back once every prepared width
-        // runs on a reconstructed copy); row ids | row pointer together, each 256-byte aligned
-        const size_t cv_bytes = (size_t)kept * sizeof(int2), ids_bytes = (size_t)R * 4, ptr_bytes = (size_t)(R + 1) * 4;
-        EPP_TRY(p->cv.alloc(cv_bytes, al));
+        // row ids | row pointer in one allocation, each 256-byte aligned
+        const size_t ids_bytes = (size_t)R * 4, ptr_bytes = (size_t)(R + 1) * 4;
         EPP_TRY(p->store.alloc(DevArena::rounded(ids_bytes) + DevArena::rounded(ptr_bytes), al));
         char* base = p->store.as<char>();
         p->row_ids.view(base, ids_bytes);
         p->rowptr.view(base + DevArena::rounded(ids_bytes), ptr_bytes);
-        // Shared entries: the path of the level before runs on this path's arrays if nearly all of
-        // this path's entries are its own too (the extra entries are skipped one by one at run time,
-        // so the inner layer pays for them; EPP_TUNE_SHARE_PCT, default 95, 0: never).  Every other
-        // level at most: a path whose marks serve an inner path keeps its own arrays.
-        epp_path* inner = nullptr;
-        if (k > 0 && kept > 0 && (int)hs.p[3] == 0) {
-            epp_path* q = built[k - 1];
-            const long long pct = env_share_pct();
-            if (pct > 0 && !q->has_inner && !q->outer && q->nnz > 0 && q->nnz * 100 >= kept * pct) inner = q;
-        }
-        if (edge_tiles) {
-            hipLaunchKernelGGL(k_edge_extract, dim3(edge_tiles), dim3(kBlock), 0, s, g->col, g->val, n_seg,
-                               mask.as<unsigned long long>(), inner ? fresh.as<unsigned long long>() : nullptr,
-                               seg_base.as<int>(), p->cv.as<int2>());
-        }
-        if (inner) {
-            EPP_TRY(p->zero_block.alloc(256, al));
-            EPP_HIP_TRY(hipMemsetAsync(p->zero_block.p, 0, 256, s));
-            p->has_inner = true;
-            inner->outer = p;
-            inner->inner_rows = P->bitmaps[k].as<unsigned int>();  // its rows are N^k
-            inner->cv.release();  // (stream-ordered: whoever gets the block next uses it on this stream or later)
-        }
         if (n > 0) {
             hipLaunchKernelGGL(k_bitmap_compact, dim3(word_tiles), dim3(kBlock), 0, s,
                                P->bitmaps[k + 1].as<unsigned long long>(), n_words, tile_base.as<int>(), newptr.as<int>(),
@@ -777,7 +780,22 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
             EPP_HIP_TRY(hipMemsetAsync(p->rowptr.p, 0, sizeof(int32_t), s));
         }
         EPP_HIP_TRY(hipGetLastError());
-        EPP_TRY(epp_path_finish(p, s, stats.p, reinterpret_cast<unsigned long long*>(hs.p) + 8 + (size_t)k * kStatWords));
+        EPP_TRY(epp_path_finish(p, s, stats.p, reinterpret_cast<unsigned long long*>(hs.p) + 8 + (size_t)k * kStatWords,
+                                /*mark_row_ends=*/false));
+        epp_path* q = pending.p;  // the path of the level before, if its entries still wait
+        if (q && nested && share_pct > 0 && q->nnz > 0 && q->nnz * 100 >= kept * share_pct) {
+            EPP_TRY(p->zero_block.alloc(256, al));
+            EPP_HIP_TRY(hipMemsetAsync(p->zero_block.p, 0, 256, s));
+            p->has_inner = true;
+            q->outer = p;
+            q->inner_rows = P->bitmaps[k].as<unsigned int>();  // its rows are N^k
+            EPP_TRY(extract(p, slot, mask[slot ^ 1].as<unsigned long long>()));
+            pending.p = nullptr;
+        } else {
+            if (q) EPP_TRY(extract(q, pending.slot, nullptr));
+            pending.p = p;
+            pending.slot = slot;
+        }
         // Fixed point: N^{k+1} == N^k means every further set is the same set, so every deeper
         // layer (rows and sources both equal to it) has exactly this path; share it.
         if (k + 1 < L && P->set_size[k + 1] == P->set_size[k]) {
@@ -802,6 +820,7 @@ extern "C" int epp_prepare(const epp_csr_t* g, const int32_t* train_ids, int64_t
             }
         }
     }
+    if (pending.p) EPP_TRY(extract(pending.p, pending.slot, nullptr));
     EPP_HIP_TRY(hipStreamSynchronize(s));
     for (size_t k = 0; k < built.size(); ++k)
         epp_path_set_stats(built[k], reinterpret_cast<const unsigned long long*>(hs.p) + 8 + k * kStatWords);
