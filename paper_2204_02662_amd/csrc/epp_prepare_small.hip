@@ -29,9 +29,31 @@ constexpr int kStatWords = EPP_NCLASS + 1; // histogram + longest row
 constexpr int kLevelWords = 3 + kStatWords; // kept entries, rows, "set did not change", statistics
 constexpr int kRowEnd = kEntRowEnd;
 constexpr int kBatch = 8;                  // independent loads in flight per lane in the streaming loops
+constexpr int kMaskBatch = 16;             // ... of the keep-mask pass (one register per load)
 
 __device__ __forceinline__ unsigned long long low_mask(int lane) { return (1ull << lane) - 1ull; }
 __device__ __forceinline__ int length_class(int len) { return len <= 1 ? 0 : 32 - __clz(len - 1); }
+
+// Position of the k-th (0-based) set bit of m (m has more than k set bits).
+__device__ __forceinline__ int select_bit(unsigned long long m, int k) {
+    int pos = 0;
+#pragma unroll
+    for (int half = 32; half >= 1; half >>= 1) {
+        const int c = __popcll(m & ((1ull << half) - 1ull));
+        if (k >= c) { k -= c; m >>= half; pos += half; }
+    }
+    return pos;
+}
+
+// Largest w in [0, count) with pre[w] <= j (pre is non-decreasing, pre[0] == 0 <= j).
+__device__ __forceinline__ int last_not_above(const int* pre, int count, int j) {
+    int lo = 0, hi = count - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (pre[mid] <= j) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
 
 // Exclusive scan of one value per thread over the workgroup; *total = sum.  (Two barriers.)
 __device__ __forceinline__ int block_scan(int x, int* wave_sum /* LDS, kWaves + 1 */, int* total) {
@@ -94,10 +116,7 @@ __global__ __launch_bounds__(kThreads) void k_prepare_small(SmallArgs a) {
         const int p0 = a.rowptr[v], p1 = a.rowptr[v + 1];
         if (p0 < 0 || p1 < p0 || p1 > a.nnz || (v == 0 && p0 != 0) || (v == a.n - 1 && p1 != a.nnz)) atomicOr(&s_err, 1);
     }
-    for (int e = tid; e < a.nnz; e += kThreads) {
-        const int c = a.col[e];
-        if (c < 0 || c >= a.n) atomicOr(&s_err, 4);
-    }
+    // (the column ids are range-checked where the first level loads them)
     __syncthreads();
     if (s_err) {  // uniform: nothing is indexed with unchecked values
         if (tid == 0) a.result[0] = s_err;
@@ -128,23 +147,33 @@ __global__ __launch_bounds__(kThreads) void k_prepare_small(SmallArgs a) {
         bm_next[tid] = 0ull;
         if (tid < EPP_NCLASS) hist[tid] = 0;
         if (tid == 0) { s_max = 0; s_differs = 0; }
-        // keep-mask of the entries: is the column in N^k?  (kBatch words per step and wavefront: the
-        // column loads of a step are issued together, their latency is paid once)
-        for (int w0 = wave * kBatch; w0 < n_seg; w0 += kWaves * kBatch) {
-            int c[kBatch];
+        // keep-mask of the entries: is the column in N^k?  (kMaskBatch words per step and wavefront:
+        // the column loads of a step are issued together, their latency is paid once.)  An id
+        // outside [0, n) is never used as an index; the first level reports it.
+        bool bad = false;
+        const unsigned int* bm32 = reinterpret_cast<const unsigned int*>(bm_cur);  // (4-byte lookups: half the bank conflicts)
+        for (int w0 = wave * kMaskBatch; w0 < n_seg; w0 += kWaves * kMaskBatch) {
+            int c[kMaskBatch];
 #pragma unroll
-            for (int i = 0; i < kBatch; ++i) {
+            for (int i = 0; i < kMaskBatch; ++i) {
                 const int e = (w0 + i) * 64 + lane;
                 c[i] = e < a.nnz ? a.col[e] : -1;
             }
 #pragma unroll
-            for (int i = 0; i < kBatch; ++i) {
-                const bool bit = c[i] >= 0 && ((bm_cur[c[i] >> 6] >> (c[i] & 63)) & 1ull);
+            for (int i = 0; i < kMaskBatch; ++i) {
+                const bool in_range = c[i] >= 0 && c[i] < a.n;
+                bad |= !in_range && (w0 + i) * 64 + lane < a.nnz;
+                const bool bit = in_range && ((bm32[c[i] >> 5] >> (c[i] & 31)) & 1u);
                 const unsigned long long m = __ballot(bit);
                 if (lane == 0 && w0 + i < n_seg) keep[w0 + i] = m;
             }
         }
+        if (k == 0 && bad) atomicOr(&s_err, 4);
         __syncthreads();
+        if (k == 0 && s_err) {  // uniform
+            if (tid == 0) a.result[0] = s_err;
+            return;
+        }
         int kept;
         {   // prefix counts of the keep-mask words: two consecutive words per thread
             const int c0 = 2 * tid < n_seg ? __popcll(keep[2 * tid]) : 0;
@@ -154,22 +183,33 @@ __global__ __launch_bounds__(kThreads) void k_prepare_small(SmallArgs a) {
             wpre[2 * tid + 1] = wbase + c0;
         }
         __syncthreads();
-        // stable compaction of (col, val)
-        for (int w0 = wave * kBatch; w0 < n_seg; w0 += kWaves * kBatch) {
+        // stable compaction of (col, val), one kept entry per thread and step: slot j of the path
+        // belongs to the word whose prefix count is the last one not above j, and is that word's
+        // (j - prefix)-th set bit.  (Walking all words instead costs a load latency per word
+        // whatever it keeps; a small training set keeps a few hundred entries out of 10^5.)
+        for (int j0 = tid; j0 < kept; j0 += kThreads * kBatch) {
+            int e[kBatch];
             int2 x[kBatch];
-            bool bit[kBatch];
 #pragma unroll
             for (int i = 0; i < kBatch; ++i) {
-                const int w = w0 + i;
-                bit[i] = w < n_seg && ((keep[w] >> lane) & 1ull);
-                if (bit[i]) x[i] = make_int2(a.col[w * 64 + lane], __float_as_int(a.val[w * 64 + lane]));
+                const int j = j0 + i * kThreads;
+                e[i] = -1;
+                if (j < kept) {
+                    const int w = last_not_above(wpre, n_seg, j);
+                    e[i] = w * 64 + select_bit(keep[w], j - wpre[w]);
+                }
             }
 #pragma unroll
             for (int i = 0; i < kBatch; ++i)
-                if (bit[i]) cv[wpre[w0 + i] + __popcll(keep[w0 + i] & low_mask(lane))] = x[i];
+                if (e[i] >= 0) x[i] = make_int2(a.col[e[i]], __float_as_int(a.val[e[i]]));
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i)
+                if (e[i] >= 0) cv[j0 + i * kThreads] = x[i];
         }
         // filtered row pointer of every vertex; a vertex with a non-empty filtered list is in N^{k+1}
-        for (int v0 = tid; v0 < a.n; v0 += kThreads * kBatch) {
+        // (the 64 lanes of a wavefront hold the 64 vertices of one bitmap word: one ballot per word)
+        int longest = 0;
+        for (int v0 = tid; v0 - lane < a.n; v0 += kThreads * kBatch) {
             int p0[kBatch], p1[kBatch];
 #pragma unroll
             for (int i = 0; i < kBatch; ++i) {
@@ -180,36 +220,38 @@ __global__ __launch_bounds__(kThreads) void k_prepare_small(SmallArgs a) {
 #pragma unroll
             for (int i = 0; i < kBatch; ++i) {
                 const int v = v0 + i * kThreads;
-                if (v >= a.n) continue;
                 const int ra = p0[i] >= a.nnz ? kept : wpre[p0[i] >> 6] + __popcll(keep[p0[i] >> 6] & low_mask(p0[i] & 63));
                 const int rb = p1[i] >= a.nnz ? kept : wpre[p1[i] >> 6] + __popcll(keep[p1[i] >> 6] & low_mask(p1[i] & 63));
-                a.newptr[v] = ra;
-                if (rb > ra) {
-                    atomicOr(&bm_next[v >> 6], 1ull << (v & 63));
+                const bool member = v < a.n && rb > ra;
+                if (v < a.n) a.newptr[v] = ra;
+                const unsigned long long word = __ballot(member);
+                if (lane == 0 && (v >> 6) < n_words) bm_next[v >> 6] = word;
+                if (member) {
                     const int len = rb - ra;
                     atomicAdd(&hist[length_class(len)], 1);
-                    atomicMax(&s_max, len);
+                    longest = max(longest, len);
                 }
             }
         }
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) longest = max(longest, __shfl_xor(longest, d, 64));
+        if (lane == 0 && longest > 0) atomicMax(&s_max, longest);
         __syncthreads();  // bm_next, newptr and the compacted entries are complete
         int R;
         const int rbase = block_scan(tid < n_words ? __popcll(bm_next[tid]) : 0, wave_sum, &R);
         rpre[tid] = rbase;
         if (tid < n_words && bm_next[tid] != bm_cur[tid]) s_differs = 1;
         __syncthreads();
-        for (int w = wave; w < n_words; w += kWaves) {
-            const unsigned long long m = bm_next[w];
-            if ((m >> lane) & 1ull) {
-                const int v = w * 64 + lane;
-                const int r = rpre[w] + __popcll(m & low_mask(lane));
-                row_ids[r] = v;
-                orp[r] = a.newptr[v];
-                // last entry of the row: one before the next vertex's first kept entry
-                const int p1 = a.rowptr[v + 1];
-                const int rb = p1 >= a.nnz ? kept : wpre[p1 >> 6] + __popcll(keep[p1 >> 6] & low_mask(p1 & 63));
-                cv[rb - 1].x |= kRowEnd;
-            }
+        // rows of the path, one per thread and step (found like the entries above)
+        for (int r = tid; r < R; r += kThreads) {
+            const int w = last_not_above(rpre, n_words, r);
+            const int v = w * 64 + select_bit(bm_next[w], r - rpre[w]);
+            row_ids[r] = v;
+            orp[r] = a.newptr[v];
+            // last entry of the row: one before the next vertex's first kept entry
+            const int p1 = a.rowptr[v + 1];
+            const int rb = p1 >= a.nnz ? kept : wpre[p1 >> 6] + __popcll(keep[p1 >> 6] & low_mask(p1 & 63));
+            cv[rb - 1].x |= kRowEnd;
         }
         long long* res = a.result + 2 + (size_t)k * kLevelWords;
         if (tid == 0) {
