@@ -49,11 +49,8 @@ def edge_bytes(R: int, nnz: int, F: int) -> int:
 
 def kernel_source_hash() -> str:
     """Hash of the HIP sources the library is built from: counter summaries are stamped with it."""
-    h = hashlib.sha256()
-    for f in sorted((ROOT / "paper_2204_02662_amd" / "csrc").glob("*")):
-        h.update(f.name.encode())
-        h.update(f.read_bytes())
-    return h.hexdigest()[:16]
+    from paper_2204_02662_amd import build as _build
+    return _build.source_hash()
 
 
 def read_traffic(workload: str):

@@ -3,6 +3,8 @@ import ctypes
 import re
 from pathlib import Path
 
+import pytest
+
 ROOT = Path(__file__).resolve().parent.parent
 
 
@@ -87,3 +89,14 @@ def test_header_is_plain_c_and_links_from_c(tmp_path):
                            "-L", str(so_dir), "-lepp", f"-Wl,-rpath,{so_dir}"])
     out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
     assert out.returncode == 0 and out.stdout.strip().endswith("ok"), out.stdout + out.stderr
+
+
+def test_built_library_is_from_the_current_sources():
+    """The library file in the tree is what the GPU tests and the benchmark load; build.py leaves the
+    hash of the sources beside it.  A file built from other sources (an edit without a rebuild, a
+    left-over experiment) would make every GPU result describe something else."""
+    from paper_2204_02662_amd import build
+    if not build.SO.exists():
+        pytest.skip("library not built")
+    assert build.STAMP.exists(), "libepp.so has no source stamp: rebuild (python -m paper_2204_02662_amd.build)"
+    assert build.STAMP.read_text().strip() == build.source_hash(), "libepp.so was built from other sources: rebuild"
