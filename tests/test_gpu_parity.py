@@ -476,6 +476,28 @@ def test_inner_path_runs_on_the_entries_of_the_next_outer_path(monkeypatch, L, l
                     assert i.n_groups >= -(-paths_o[l - 1].col.size // 24)  # groups of the outer path's entries
         assert_paths_bit_exact(paths, sets_o, paths_o, L)
         held[pct] = sum(paths.path(l).info().bytes for l in range(L))
+        if pct == "1":
+            # the launches of the inner path captured in a HIP graph: replays reproduce the eager result
+            l, F = L - 1, 128
+            p = paths.path(l)
+            p.prepare_width(F)
+            gin = torch.from_numpy(graphgen.normal_rows(g.n, F, sets_o[L - l - 1], 379)).to(dev())
+            gout = torch.zeros_like(gin)
+            epp.epp_backward_aggregate(p, gin, gout)
+            torch.cuda.synchronize()
+            eager = gout.clone()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                epp.epp_backward_aggregate(p, gin, gout)
+            rows_t = torch.from_numpy(sets_o[L - l].astype(bool)).to(dev())
+            for rep in range(3):
+                gout.fill_(float(rep))
+                torch.cuda.synchronize()
+                graph.replay()
+                torch.cuda.synchronize()
+                assert torch.equal(gout[rows_t], eager[rows_t]), f"replay {rep}"
+                assert torch.all(gout[~rows_t] == float(rep)), f"replay {rep}: row outside the path written"
+            del graph
     # the shared path holds row ids and row pointer only
     assert held["1"] <= held["0"] - 8 * paths_o[L - 1].col.size + (1 << 16), held
 
