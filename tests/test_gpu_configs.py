@@ -29,9 +29,18 @@ def assert_close_all_rows(got, want, what):
         assert_close(got[a:a + CHUNK], want[a:a + CHUNK], f"{what}, rows {a}..")
 
 
+# (configuration, EPP_TUNE_SHARE_PCT or None for the library's own rule, layers expected to run on the
+# entry array of the next outer layer).  Configurations 4 and 5 share by themselves; on configuration 3
+# the inner path holds two thirds of the outer one's entries, and forcing the sharing there runs the
+# entry-skipping kernels at full size with a third of the entries skipped.
+CASES = [(3, None, []), (3, "50", [1]), (4, None, [1]), (5, None, [1])]
+
+
 @pytest.mark.timeout(900)
-@pytest.mark.parametrize("k", [3, 4, 5])
-def test_large_config(k):
+@pytest.mark.parametrize("k,share_pct,shared_layers", CASES)
+def test_large_config(k, share_pct, shared_layers, monkeypatch):
+    if share_pct is not None:
+        monkeypatch.setenv("EPP_TUNE_SHARE_PCT", share_pct)
     print(f"[cfg {k}] generating", flush=True)
     cfg = graphgen.make_config(k)
     g, L = cfg.graph, cfg.L
@@ -40,6 +49,7 @@ def test_large_config(k):
     print(f"[cfg {k}] gpu prepare", flush=True)
     paths = gpu_prepare(g, cfg.train_ids, L)
     assert_paths_bit_exact(paths, sets_o, paths_o, L)
+    assert [l for l in range(L) if paths.path(l).info().shares_entries] == shared_layers
     full = gpu_prepare_full(g)
     colsum = np.zeros(g.n, np.float64)
     np.add.at(colsum, g.col, g.val.astype(np.float64))
