@@ -1,4 +1,4 @@
-"""Measurement studies around the hot path (they need a GPU):
+"""Measurement studies around the hot path (they need a GPU unless noted):
 
     python -m paper_2204_02662_amd.studies gs    --config 4          # group-size sweep per layer (Sec. 5, Fig. 4 analogue)
     python -m paper_2204_02662_amd.studies depth --config 4 --F 64   # L = 2..6 (multi-layer study, Fig. 10 analogue)
@@ -6,6 +6,8 @@
     python -m paper_2204_02662_amd.studies overlap --config 5        # path preparing hidden behind the forward pass
     python -m paper_2204_02662_amd.studies gsfit                      # regression for the group size re-fitted on a
                                                                       # generated corpus (Sec. 5's method on wave64)
+    python -m paper_2204_02662_amd.studies l2model --config 5 --F 128 # expected L2 hit rate of the gathers from the
+                                                                      # graph's reference counts (no GPU needed)
 
 Both print one JSON object per measurement.  Synthetic inputs only (graphgen).
 """
@@ -334,9 +336,48 @@ def gsfit_study(args):
           flush=True)
 
 
+def l2model_study(args):
+    """What hit rate can one XCD's 4 MB L2 reach on the source rows of a graph?  From the reference
+    counts alone (CPU only): the share of the references that goes to the C most referenced rows (a
+    cache that held exactly those), and the hit rate of an LRU cache of C rows under the
+    independent-reference model (Che's approximation: a row referenced with rate p hits with
+    probability 1 - exp(-p T), where T makes the expected number of resident rows equal C), with
+    all sources competing for the cache and with only the unstreamed ones (the hot/cold budget)."""
+    import numpy as np
+
+    import graphgen
+
+    g = graphgen.make_config(args.config).graph
+    cnt = np.sort(np.bincount(g.col, minlength=g.n).astype(np.float64))[::-1]
+    nnz = cnt.sum()
+
+    def lru_hit_rate(c, rows):
+        resident = lambda t: (1.0 - np.exp(-c * t)).sum()
+        lo, hi = 0.0, 1.0
+        while resident(hi) < rows:
+            hi *= 2
+        for _ in range(80):
+            mid = 0.5 * (lo + hi)
+            lo, hi = (mid, hi) if resident(mid) < rows else (lo, mid)
+        t = 0.5 * (lo + hi)
+        return float((c * (1.0 - np.exp(-c * t))).sum() / nnz)
+
+    row_bytes = 4 * args.F
+    unstreamed = cnt[:(96 << 20) // row_bytes]
+    for slices in (1, 2):
+        rows = (4 << 20) * slices // row_bytes
+        print(json.dumps({"config": args.config, "F": args.F, "xcd_feature_slices": slices, "rows_one_l2_holds": rows,
+                          "share_of_references_to_that_many_top_rows": float(cnt[:rows].sum() / nnz),
+                          "lru_hit_rate_all_sources_compete": lru_hit_rate(cnt, rows),
+                          "lru_hit_rate_only_unstreamed_sources_compete": lru_hit_rate(unstreamed, rows)}), flush=True)
+    part_rows = 8 * (3584 << 10) // row_bytes
+    print(json.dumps({"config": args.config, "F": args.F, "rows_eight_l2s_hold_together": part_rows,
+                      "share_of_references_to_that_many_top_rows": float(cnt[:part_rows].sum() / nnz)}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("study", choices=["gs", "depth", "combine", "gsfit", "overlap", "shape"])
+    ap.add_argument("study", choices=["gs", "depth", "combine", "gsfit", "overlap", "shape", "l2model"])
     ap.add_argument("--config", type=int, default=4)
     ap.add_argument("--F", type=int, default=64)
     ap.add_argument("--Fo", type=int, default=128)
@@ -345,6 +386,8 @@ def main():
     ap.add_argument("--log2n", type=lambda v: [int(x) for x in v.split(",")], default=[13, 15, 17, 19])
     ap.add_argument("--widths", type=lambda v: [int(x) for x in v.split(",")], default=[16, 64, 128])
     args = ap.parse_args()
+    if args.study == "l2model":
+        return l2model_study(args)
     import torch
 
     assert torch.cuda.is_available(), "the studies need a GPU"
