@@ -797,23 +797,19 @@ int epp_tune_locality(epp_path* p, int F, int gs, hipStream_t s, int* log2_slice
         return c < 1 ? 1 : bin_floor(c + 1 == 4 ? 8 : c + 1);  // bins 1..c are left out
     };
 
-    if (want_cold) {
+    // One set of marks per path, shared by all its widths: it is the one chosen for the largest
+    // prepared width that marks at all (a smaller budget in rows; narrower widths then stream a
+    // few rows they could have kept).  The marks therefore depend on which widths have been
+    // prepared, never on the order of the calls.
+    int new_thr = 0;  // > 0: the marks have to be set anew with this threshold
+    if (want_cold && F > p->cold_F) {
+        p->cold_F = F;
         const int thr = threshold_for(rows_budget);
-        // One set of marks per path, shared by all its widths: it is the one chosen for the largest
-        // prepared width that marks at all (a smaller budget in rows; narrower widths then stream a
-        // few rows they could have kept).  The marks therefore depend on which widths have been
-        // prepared, never on the order of the calls.
-        if (F > p->cold_F) {
-            p->cold_F = F;
-            if (thr != p->cold_thr) {
-                hipLaunchKernelGGL(k_hot_bitmap, dim3((unsigned)((p->n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
-                                   cnt.as<int>(), p->n, thr, hot.as<unsigned long long>());
-                hipLaunchKernelGGL(k_mark_cold, dim3((unsigned)((p->nnz + 2 * kBlock - 1) / (2 * kBlock))), dim3(kBlock),
-                                   0, s, reinterpret_cast<int2v*>(p->cv.p), p->nnz, hot.as<unsigned int>());
-                EPP_HIP_TRY(hipGetLastError());
-                EPP_HIP_TRY(hipStreamSynchronize(s));
-                p->cold_thr = thr;
-            }
+        if (thr != p->cold_thr) {
+            new_thr = thr;
+            hipLaunchKernelGGL(k_hot_bitmap, dim3((unsigned)((p->n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
+                               cnt.as<int>(), p->n, thr, hot.as<unsigned long long>());
+            EPP_HIP_TRY(hipGetLastError());
         }
     }
 
@@ -823,8 +819,22 @@ int epp_tune_locality(epp_path* p, int F, int gs, hipStream_t s, int* log2_slice
             hipLaunchKernelGGL(k_hot_bitmap, dim3((unsigned)((p->n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s,
                                cnt.as<int>(), p->n, thr, part_hot.as<unsigned long long>());
             EPP_HIP_TRY(hipGetLastError());
-            EPP_TRY(epp_build_partition(p, F, gs, part_hot.as<unsigned int>(), s, part));
+            // (new marks are set by the copy itself, from the bitmap)
+            EPP_TRY(epp_build_partition(p, F, gs, part_hot.as<unsigned int>(), new_thr > 0 ? hot.as<unsigned int>() : nullptr,
+                                        s, part));
         }
+    }
+
+    if (new_thr > 0) {
+        // The canonical array needs the new marks only if something will still read it: not when it
+        // is given back right after this width is prepared (a rebuilt one takes the marks of the copy).
+        if (!(*part && epp_canonical_unused(p, F))) {
+            hipLaunchKernelGGL(k_mark_cold, dim3((unsigned)((p->nnz + 2 * kBlock - 1) / (2 * kBlock))), dim3(kBlock), 0, s,
+                               reinterpret_cast<int2v*>(p->cv.p), p->nnz, hot.as<unsigned int>());
+            EPP_HIP_TRY(hipGetLastError());
+        }
+        EPP_HIP_TRY(hipStreamSynchronize(s));
+        p->cold_thr = new_thr;
     }
 
     // (chosen whether or not the width has a partitioned layout: the if-else baseline never uses that layout)

@@ -316,12 +316,17 @@ int epp_tune_locality(epp_path* p, int F, int gs, hipStream_t s, int* log2_slice
 // partition.hip
 int epp_partition_hot_rows(int F);  // source rows of width F the eight L2s hold together
 // source-partitioned layout of `p` for width F and group size gs, or *out = NULL where it does not pay
-int epp_build_partition(epp_path* p, int F, int gs, const unsigned int* hot_bitmap, hipStream_t s, Partition** out);
+// `unstreamed` (or NULL): bitmap of the sources whose entries stay unmarked in the last section; the
+// copy then sets the streamed-source marks itself, whatever the canonical array carries
+int epp_build_partition(epp_path* p, int F, int gs, const unsigned int* hot_bitmap, const unsigned int* unstreamed,
+                        hipStream_t s, Partition** out);
 
 // partition.hip: canonical entry array of `p` rebuilt from a reconstructed copy, if it was given back
 int epp_ensure_canonical(epp_path* p, hipStream_t s);
 // gives the canonical entry array back if every prepared width runs on a reconstructed copy
 void epp_release_canonical_if_unused(epp_path* p);
+// would it be given back if width F_with_copy (0: none) had a reconstructed copy and were prepared?
+bool epp_canonical_unused(const epp_path* p, int F_with_copy);
 
 // prepare.hip: exclusive scan of n ints (*total, device, receives the sum); tmp: epp_scan_tmp_bytes(n)
 size_t epp_scan_tmp_bytes(int64_t n);

@@ -207,13 +207,16 @@ __global__ __launch_bounds__(kBlock) void k_part_vrows(int64_t R, int64_t M, int
 
 // One wavefront per tile: every entry to its section, in the row's order; the last entry of the
 // row's share of a section carries the row-end flag; the streamed-source mark survives only in the
-// last section (the hot sections are gathered with plain loads throughout).
+// last section (the hot sections are gathered with plain loads throughout).  With `unstreamed` (one
+// bit per source that stays unmarked) the marks are set here instead of being copied: the caller
+// then need not mark the canonical array first, a pass over all entries of its own.
 __global__ __launch_bounds__(kBlock) void k_part_scatter_cut(const int2v* __restrict__ cv,
                                                              const int32_t* __restrict__ rowptr,
                                                              const int32_t* __restrict__ srow,
                                                              const int32_t* __restrict__ tile_row,
                                                              const int* __restrict__ tile_first, int64_t M, int64_t T,
                                                              const unsigned int* __restrict__ hot,
+                                                             const unsigned int* __restrict__ unstreamed,
                                                              const int* __restrict__ toff, const int* __restrict__ voff,
                                                              const int* __restrict__ klen, int2v* __restrict__ cv2,
                                                              const int* __restrict__ sec_off,
@@ -260,7 +263,12 @@ __global__ __launch_bounds__(kBlock) void k_part_scatter_cut(const int2v* __rest
         }
         if (sec[i] >= 0) {
             int2v e = ent[i];
-            e.x = (e.x & (kColMask | kOuterOnly)) | (sec[i] == kHot ? (e.x & kCold) : 0) | (last ? kRowEnd : 0);
+            int cold = e.x & kCold;
+            if (unstreamed && sec[i] == kHot) {
+                const int c = e.x & kColMask;
+                cold = ((unstreamed[c >> 5] >> (c & 31)) & 1u) ? 0 : kCold;
+            }
+            e.x = (e.x & (kColMask | kOuterOnly)) | (sec[i] == kHot ? cold : 0) | (last ? kRowEnd : 0);
             cv2[dest] = e;
         }
         // the section ids, two to a byte (an even lane writes its own and its neighbour's): they are
@@ -315,32 +323,47 @@ __global__ __launch_bounds__(kBlock) void k_part_gather_cut(const int2v* __restr
     }
 }
 
+// (Eight lanes per row: a row's entries are consecutive on both sides, so the lanes of a row move
+// 64 contiguous bytes per step.)
+constexpr int kRowLanes = 8;
+
 __global__ __launch_bounds__(kBlock) void k_part_gather_whole(const int2v* __restrict__ cv2,
                                                               const int32_t* __restrict__ rowptr, int64_t R,
                                                               const int* __restrict__ whole_off, int2v* __restrict__ cv) {
-    const int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int64_t r = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / kRowLanes;
     if (r >= R || whole_off[r] < 0) return;
     const int p0 = rowptr[r], p1 = rowptr[r + 1];
     const int2v* __restrict__ src = cv2 + whole_off[r];
-    for (int j = p0; j < p1; ++j) cv[j] = src[j - p0];
+    for (int j = p0 + (threadIdx.x & (kRowLanes - 1)); j < p1; j += kRowLanes) cv[j] = src[j - p0];
 }
 
-// Rows that are not cut: copied as they are (flags included) to their place at the end of the last section.
+// Rows that are not cut: copied to their place at the end of the last section, flags included; with
+// `unstreamed` the streamed-source marks are set from that bitmap instead (see k_part_scatter_cut).
 __global__ __launch_bounds__(kBlock) void k_part_scatter_whole(const int2v* __restrict__ cv,
                                                                const int32_t* __restrict__ rowptr, int64_t R, int64_t M,
                                                                const int32_t* __restrict__ m_of_row,
-                                                               const int* __restrict__ voff, int2v* __restrict__ cv2,
-                                                               int* __restrict__ whole_off) {
-    const int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+                                                               const int* __restrict__ voff,
+                                                               const unsigned int* __restrict__ unstreamed,
+                                                               int2v* __restrict__ cv2, int* __restrict__ whole_off) {
+    const int64_t r = ((int64_t)blockIdx.x * kBlock + threadIdx.x) / kRowLanes;
     if (r >= R) return;
+    const int sub = threadIdx.x & (kRowLanes - 1);
     if (m_of_row[r] >= 0) {
-        whole_off[r] = -1;
+        if (sub == 0) whole_off[r] = -1;
         return;
     }
     const int p0 = rowptr[r], p1 = rowptr[r + 1];
-    whole_off[r] = voff[kSec * M + r];
-    int2v* __restrict__ d = cv2 + voff[kSec * M + r];
-    for (int j = p0; j < p1; ++j) d[j - p0] = cv[j];
+    const int at = voff[kSec * M + r];
+    if (sub == 0) whole_off[r] = at;
+    int2v* __restrict__ d = cv2 + at;
+    for (int j = p0 + sub; j < p1; j += kRowLanes) {
+        int2v e = cv[j];
+        if (unstreamed) {
+            const int c = e.x & kColMask;
+            e.x = (e.x & ~kCold) | (((unstreamed[c >> 5] >> (c & 31)) & 1u) ? 0 : kCold);
+        }
+        d[j - p0] = e;
+    }
 }
 
 inline unsigned grid_for(int64_t n, int per_block) { return (unsigned)std::max<int64_t>((n + per_block - 1) / per_block, 1); }
@@ -358,7 +381,8 @@ int epp_partition_hot_rows(int F) {
     return (int)std::min<int64_t>(kHot * kb_per_xcd * 1024 / ((int64_t)F * 4), 1 << 30);
 }
 
-int epp_build_partition(epp_path* p, int F, int gs, const unsigned int* hot_bitmap, hipStream_t s, Partition** out) {
+int epp_build_partition(epp_path* p, int F, int gs, const unsigned int* hot_bitmap, const unsigned int* unstreamed,
+                        hipStream_t s, Partition** out) {
     *out = nullptr;
     const int mode = env_int("EPP_TUNE_PART", 1);  // 0: never, 1: where it pays, 2: always (tests)
     if (mode == 0 || p->nnz == 0 || p->n_stream_rows == 0) return EPP_OK;
@@ -500,11 +524,12 @@ int epp_build_partition(epp_path* p, int F, int gs, const unsigned int* hot_bitm
                        n_vrows, (int)nnz, q->vptr.as<int32_t>(), q->tgt.as<int32_t>(), q->mvert.as<int32_t>(),
                        sec_start.as<int>());
     hipLaunchKernelGGL(k_part_scatter_cut, dim3(grid_for(T, kBlock / 64)), dim3(kBlock), 0, s, cv, rowptr,
-                       srow.as<int32_t>(), tile_row.as<int32_t>(), tile_first.as<int>(), M, T, hot_bitmap, toff.as<int>(),
+                       srow.as<int32_t>(), tile_row.as<int32_t>(), tile_first.as<int>(), M, T, hot_bitmap, unstreamed,
+                       toff.as<int>(),
                        voff.as<int>(), klen.as<int>(), reinterpret_cast<int2v*>(q->cv2.p), sec_off.as<int>(),
                        q->sec4.as<unsigned char>());
-    hipLaunchKernelGGL(k_part_scatter_whole, dim3(grid_for(R, kBlock)), dim3(kBlock), 0, s, cv, rowptr, R, M,
-                       m_of_row.as<int32_t>(), voff.as<int>(), reinterpret_cast<int2v*>(q->cv2.p),
+    hipLaunchKernelGGL(k_part_scatter_whole, dim3(grid_for(R * kRowLanes, kBlock)), dim3(kBlock), 0, s, cv, rowptr, R, M,
+                       m_of_row.as<int32_t>(), voff.as<int>(), unstreamed, reinterpret_cast<int2v*>(q->cv2.p),
                        q->whole_off.as<int>());
     EPP_HIP_TRY(hipGetLastError());
     int h_sec[kSec];
@@ -524,15 +549,21 @@ int epp_build_partition(epp_path* p, int F, int gs, const unsigned int* hot_bitm
 // (other than the all-active graph, which also serves the if-else baseline) runs on its reconstructed
 // copy, the canonical array is given back to the allocator; it is rebuilt from a copy, bit for bit,
 // the next time one of those needs it.
-void epp_release_canonical_if_unused(epp_path* p) {
+bool epp_canonical_unused(const epp_path* p, int F_with_copy) {
     const char* e = std::getenv("EPP_TUNE_KEEP_CANONICAL");
-    if (e && e[0] == '1') return;
-    if (p->all_rows || !p->cv.p || !p->cv.owned || p->widths.empty()) return;
-    for (const auto& w : p->widths)
-        if (w.sched && !w.part) return;  // a width that launches on the canonical array
-    bool any = false;
-    for (const auto& w : p->widths) any |= (w.part != nullptr);
-    if (any) p->cv.release();
+    if (e && e[0] == '1') return false;
+    if (p->all_rows || !p->cv.p || !p->cv.owned) return false;
+    bool any = F_with_copy > 0;
+    for (const auto& w : p->widths) {
+        if (w.F == F_with_copy) continue;
+        if (w.sched && !w.part) return false;  // a width that launches on the canonical array
+        any |= (w.part != nullptr);
+    }
+    return any;
+}
+
+void epp_release_canonical_if_unused(epp_path* p) {
+    if (epp_canonical_unused(p, 0)) p->cv.release();
 }
 
 int epp_ensure_canonical(epp_path* p, hipStream_t s) {
@@ -547,7 +578,7 @@ int epp_ensure_canonical(epp_path* p, hipStream_t s) {
     hipLaunchKernelGGL(k_part_gather_cut, dim3(grid_for(q->n_tiles, kBlock / 64)), dim3(kBlock), 0, s, cv2,
                        p->rowptr.as<int32_t>(), q->srow.as<int32_t>(), q->tile_row.as<int32_t>(), q->tile_first.as<int>(),
                        q->n_tiles, q->toff.as<int>(), q->sec_off.as<int>(), q->sec4.as<unsigned char>(), cv);
-    hipLaunchKernelGGL(k_part_gather_whole, dim3(grid_for(p->n_stream_rows, kBlock)), dim3(kBlock), 0, s, cv2,
+    hipLaunchKernelGGL(k_part_gather_whole, dim3(grid_for(p->n_stream_rows * kRowLanes, kBlock)), dim3(kBlock), 0, s, cv2,
                        p->rowptr.as<int32_t>(), p->n_stream_rows, q->whole_off.as<int>(), cv);
     EPP_HIP_TRY(hipGetLastError());
     return EPP_OK;

@@ -402,6 +402,9 @@ def test_canonical_entries_are_given_back_and_rebuilt(monkeypatch):
     monkeypatch.setenv("EPP_TUNE_PART", "2")
     monkeypatch.setenv("EPP_TUNE_PART_KB", "64")
     monkeypatch.setenv("EPP_TUNE_PART_MINLEN", "8")
+    # (with streamed-source marks: set by the copy itself where the canonical array is about to be given
+    # back, on the canonical array where it stays)
+    monkeypatch.setenv("EPP_TUNE_HOT_MB", "1")
     held = {}
     for keep in ("1", "0"):
         monkeypatch.setenv("EPP_TUNE_KEEP_CANONICAL", keep)
