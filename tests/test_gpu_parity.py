@@ -640,10 +640,12 @@ def test_epoch_captured_in_a_hip_graph_replays_correctly():
             assert torch.equal(ys[l][~rows[l]], keep[l])  # rows outside the path untouched
 
 
-def test_randomised_shapes(construction):
-    """Many small random problems: graph shape, direction, self-loops, depth, width, group size."""
+def test_randomised_shapes(construction, monkeypatch):
+    """Many small random problems: graph shape, direction, self-loops, depth, width, group size, and
+    (general construction) how readily consecutive paths share their entries."""
     rng = np.random.default_rng(2024)
     for case in range(60):
+        monkeypatch.setenv("EPP_TUNE_SHARE_PCT", str((95, 1, 50, 0)[case % 4]))
         n = int(rng.integers(1, 700))
         m = int(rng.integers(0, 6 * n + 1))
         sym = bool(rng.integers(0, 2))
