@@ -336,6 +336,26 @@ def gsfit_study(args):
           flush=True)
 
 
+def lru_hit_rate_irm(counts, rows: int) -> float:
+    """Hit rate of an LRU cache of `rows` places when item i is referenced with probability
+    proportional to counts[i], independently of the past (Che's approximation)."""
+    import numpy as np
+
+    c = np.asarray(counts, np.float64)
+    c = c[c > 0]
+    if rows >= c.size:
+        return 1.0
+    resident = lambda t: (1.0 - np.exp(-c * t)).sum()
+    lo, hi = 0.0, 1.0 / c.max()
+    while resident(hi) < rows:
+        hi *= 2
+    for _ in range(100):
+        mid = 0.5 * (lo + hi)
+        lo, hi = (mid, hi) if resident(mid) < rows else (lo, mid)
+    t = 0.5 * (lo + hi)
+    return float((c * (1.0 - np.exp(-c * t))).sum() / c.sum())
+
+
 def l2model_study(args):
     """What hit rate can one XCD's 4 MB L2 reach on the source rows of a graph?  From the reference
     counts alone (CPU only): the share of the references that goes to the C most referenced rows (a
@@ -351,16 +371,8 @@ def l2model_study(args):
     cnt = np.sort(np.bincount(g.col, minlength=g.n).astype(np.float64))[::-1]
     nnz = cnt.sum()
 
-    def lru_hit_rate(c, rows):
-        resident = lambda t: (1.0 - np.exp(-c * t)).sum()
-        lo, hi = 0.0, 1.0
-        while resident(hi) < rows:
-            hi *= 2
-        for _ in range(80):
-            mid = 0.5 * (lo + hi)
-            lo, hi = (mid, hi) if resident(mid) < rows else (lo, mid)
-        t = 0.5 * (lo + hi)
-        return float((c * (1.0 - np.exp(-c * t))).sum() / nnz)
+    def lru_hit_rate(c, rows):  # (as a share of ALL references: streamed sources never hit)
+        return lru_hit_rate_irm(c, rows) * float(c.sum() / nnz)
 
     row_bytes = 4 * args.F
     unstreamed = cnt[:(96 << 20) // row_bytes]
